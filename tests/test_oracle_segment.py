@@ -1,0 +1,339 @@
+"""Pins for the oracle's segment training step (paper Sec. 2 and 3).  CPU only.
+
+Each test fixes the oracle to something other than itself: numbers the paper
+prints, hand arithmetic, closed forms, finite differences, or an automatic-
+differentiation library run in float64."""
+
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rng
+from oracle import segment as osg
+from paper_2403_11204_amd import datagen
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+ACTS = {"relu_all": osg.RELU_ALL, "identity_last": osg.RELU_HIDDEN_IDENTITY_LAST}
+
+
+def _rand_segment(widths, act, loss, seed, **kw):
+    seg = osg.Segment(widths, act, loss, **kw)
+    for l, (W, b) in enumerate(datagen.uniform_weights(widths, seed)):
+        seg.set_params(l, W, b)
+    return seg
+
+
+# ---------------------------------------------------------------------------------
+# numbers the paper prints (Sec. 3)
+# ---------------------------------------------------------------------------------
+def test_paper_parameter_and_mac_counts():
+    seen = 0
+    for line in open(os.path.join(GOLDEN, "paper_sec3_counts.txt")):
+        f = line.split()
+        if not f or f[0] not in ("left", "right"):
+            continue
+        widths = [int(x) for x in f[1].split(",")]
+        assert osg.param_count(widths) == int(f[3])
+        assert osg.mac_count(widths, ACTS[f[2]]) == int(f[4])
+        seen += 1
+    assert seen == 2
+    # the cut layer carries a ReLU, the network's last layer does not: flipping
+    # either convention breaks the printed MAC counts
+    assert osg.mac_count([784, 80, 60], osg.RELU_HIDDEN_IDENTITY_LAST) != 67800
+    assert osg.mac_count([60, 60, 60, 47], osg.RELU_ALL) != 10307
+    assert osg.gemm_flops_per_sample([784, 1024, 1024, 512]) == 12648448
+
+
+# ---------------------------------------------------------------------------------
+# forward
+# ---------------------------------------------------------------------------------
+def test_forward_hand_worked():
+    # 2 -> 2 -> 1, worked by hand
+    seg = osg.Segment([2, 2, 1], osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT)
+    seg.set_params(0, np.array([[1.0, -2.0], [0.5, 0.25]]), np.array([0.5, -1.0]))
+    seg.set_params(1, np.array([[2.0, -3.0]]), np.array([0.25]))
+    X = np.array([[1.0, 1.0], [2.0, 4.0]])
+    # row 0: z1 = (1-2+.5, .5+.25-1) = (-.5, -.25) -> a1 = (0,0) -> z2 = .25
+    # row 1: z1 = (2-8+.5, 1+1-1) = (-5.5, 1) -> a1 = (0,1) -> z2 = -3+.25 = -2.75
+    A, Z = seg.forward_all(X)
+    assert np.array_equal(Z[1], [[-0.5, -0.25], [-5.5, 1.0]])
+    assert np.array_equal(A[1], [[0.0, 0.0], [0.0, 1.0]])
+    assert np.array_equal(A[2], [[0.25], [-2.75]])
+    # same weights, ReLU on the last layer too
+    seg2 = osg.Segment([2, 2, 1], osg.RELU_ALL, osg.MSE_SIL)
+    seg2.set_params(0, seg.W[0], seg.b[0])
+    seg2.set_params(1, seg.W[1], seg.b[1])
+    assert np.array_equal(seg2.forward(X), [[0.25], [0.0]])
+
+
+def test_forward_special_weights():
+    g = np.random.default_rng(0)
+    X = g.standard_normal((5, 6))
+    seg = osg.Segment([6, 6, 6], osg.RELU_ALL, osg.MSE_SIL)
+    bias = g.standard_normal(6)
+    seg.set_params(1, np.zeros((6, 6)), bias)             # W = 0 -> act(b)
+    assert np.array_equal(seg.forward(X), np.tile(np.maximum(bias, 0), (5, 1)))
+    seg.set_params(0, np.eye(6), np.zeros(6))             # identity -> relu(x)
+    seg.set_params(1, np.eye(6), np.zeros(6))
+    assert np.array_equal(seg.forward(X), np.maximum(X, 0))
+    # W is [out, in]: a non-square, non-symmetric case catches a transposed operand
+    seg = osg.Segment([3, 2], osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT)
+    seg.set_params(0, np.array([[1.0, 2.0, 3.0], [0.0, -1.0, 0.5]]), np.zeros(2))
+    assert np.array_equal(seg.forward(np.array([[1.0, 10.0, 100.0]])), [[321.0, 40.0]])
+
+
+# ---------------------------------------------------------------------------------
+# losses: closed forms and brute force
+# ---------------------------------------------------------------------------------
+def test_mse_closed_forms():
+    T = rng.make_synthetic_labels(13, 47, 32, rng.BINARY_PM1).astype(np.float64)
+    y = datagen.balanced_classes(20, 47)
+    seg = osg.Segment([8, 32], osg.RELU_ALL, osg.MSE_SIL)       # W = 0, b = 0
+    out = seg.step(np.ones((20, 8)), y, T, update=False)
+    assert out["loss"] == 1.0                                    # mean of (+-1)^2
+    assert np.all(out["dZ"][1] == 0)                             # ReLU'(0) = 0
+    # brute force with python loops on random activations
+    g = np.random.default_rng(1)
+    AL = g.standard_normal((4, 5))
+    Tt = g.standard_normal((3, 5))
+    yy = np.array([2, 0, 2, 1])
+    loss, G = seg.loss_and_grad(AL, yy, Tt)
+    s = 0.0
+    for n in range(4):
+        for i in range(5):
+            d = AL[n, i] - Tt[yy[n], i]
+            s += d * d
+            assert math.isclose(G[n, i], 2 * d / 20, rel_tol=1e-14)
+    assert math.isclose(loss, s / 20, rel_tol=1e-14)
+
+
+@pytest.mark.parametrize("C", [47, 100, 1000])
+def test_cross_entropy_closed_forms(C):
+    seg = osg.Segment([4, C], osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT)
+    B = 6
+    y = np.array([0, 1, C - 1, 5, 5, 2])
+    loss, G = seg.loss_and_grad(np.zeros((B, C)), y)
+    assert math.isclose(loss, math.log(C), rel_tol=1e-14)
+    expect = np.full((B, C), 1.0 / C)
+    expect[np.arange(B), y] -= 1.0
+    assert np.allclose(G, expect / B, rtol=1e-14, atol=0)
+    g = np.random.default_rng(2)
+    Zl = 5 * g.standard_normal((B, C))
+    loss1, G1 = seg.loss_and_grad(Zl, y)
+    loss2, G2 = seg.loss_and_grad(Zl + 1000.0, y)              # shift invariance, no overflow
+    assert math.isclose(loss1, loss2, rel_tol=1e-9) and np.allclose(G1, G2, atol=1e-12)
+    assert np.allclose(G1.sum(axis=1), 0, atol=1e-15)           # rows of dZ sum to zero
+    p = G1 * B
+    p[np.arange(B), y] += 1
+    assert np.allclose(p.sum(axis=1), 1) and np.all(p > 0)
+    # brute force
+    s = 0.0
+    for n in range(B):
+        s += math.log(sum(math.exp(v) for v in Zl[n])) - Zl[n, y[n]]
+    assert math.isclose(loss1, s / B, rel_tol=1e-12)
+
+
+# ---------------------------------------------------------------------------------
+# gradients
+# ---------------------------------------------------------------------------------
+def _loss_only(seg, X, y, T):
+    A, _ = seg.forward_all(X)
+    return seg.loss_and_grad(A[-1], y, T)[0]
+
+
+@pytest.mark.parametrize("act,loss", [(osg.RELU_ALL, osg.MSE_SIL), (osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT),
+                                      (osg.RELU_HIDDEN_IDENTITY_LAST, osg.MSE_SIL), (osg.RELU_ALL, osg.SOFTMAX_XENT)])
+def test_gradients_central_differences(act, loss):
+    widths = [5, 4, 6, 3]
+    seg = _rand_segment(widths, act, loss, seed=4)
+    g = np.random.default_rng(3)
+    X = g.uniform(0, 1, (3, 5))
+    y = np.array([2, 0, 1])
+    T = g.uniform(0, 1, (3, 3))
+    out = seg.step(X, y, T, update=False)
+    h = 1e-6
+    for l in range(seg.L):
+        for arr, grad in ((seg.W[l], out["dW"][l]), (seg.b[l], out["db"][l])):
+            it = np.nditer(arr, flags=["multi_index"])
+            for _ in it:
+                idx = it.multi_index
+                keep = arr[idx]
+                arr[idx] = keep + h
+                lp = _loss_only(seg, X, y, T)
+                arr[idx] = keep - h
+                lm = _loss_only(seg, X, y, T)
+                arr[idx] = keep
+                assert abs((lp - lm) / (2 * h) - grad[idx]) < 1e-7, (l, idx)
+    assert out["dZ"][0] is None       # nothing flows out of the segment's first layer
+
+
+@pytest.mark.parametrize("act,loss,mu", [(osg.RELU_ALL, osg.MSE_SIL, 0.9), (osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT, 0.9),
+                                         (osg.RELU_ALL, osg.MSE_SIL, 0.0)])
+def test_steps_against_autodiff_library(act, loss, mu):
+    """Three consecutive steps against torch autograd + torch.optim.SGD in
+    float64: pins forward, both losses, every gradient, the momentum convention
+    (the paper trains with that framework's SGD, Sec. 3) and the update sign."""
+    widths = [7, 9, 8, 5]
+    seg = _rand_segment(widths, act, loss, seed=8, lr=0.05, momentum=mu)
+    tW = [torch.tensor(w.copy(), dtype=torch.float64, requires_grad=True) for w in seg.W]
+    tb = [torch.tensor(b.copy(), dtype=torch.float64, requires_grad=True) for b in seg.b]
+    opt = torch.optim.SGD(tW + tb, lr=0.05, momentum=mu)
+    g = np.random.default_rng(6)
+    T = g.uniform(0, 2, (5, 5))
+    for it in range(3):
+        X = g.uniform(0, 1, (6, 7))
+        y = g.integers(0, 5, 6)
+        out = seg.step(X, y, T)
+        a = torch.tensor(X)
+        for l in range(3):
+            a = a @ tW[l].T + tb[l]
+            if l < 2 or act == osg.RELU_ALL:
+                a = torch.relu(a)
+        if loss == osg.MSE_SIL:
+            lt = torch.nn.functional.mse_loss(a, torch.tensor(T[y]))
+        else:
+            lt = torch.nn.functional.cross_entropy(a, torch.tensor(y))
+        opt.zero_grad()
+        lt.backward()
+        assert math.isclose(out["loss"], lt.item(), rel_tol=1e-12)
+        for l in range(3):
+            assert np.allclose(out["dW"][l], tW[l].grad.numpy(), rtol=1e-10, atol=1e-14)
+            assert np.allclose(out["db"][l], tb[l].grad.numpy(), rtol=1e-10, atol=1e-14)
+        opt.step()
+        for l in range(3):
+            assert np.allclose(seg.W[l], tW[l].detach().numpy(), rtol=1e-12, atol=1e-15)
+            assert np.allclose(seg.b[l], tb[l].detach().numpy(), rtol=1e-12, atol=1e-15)
+
+
+def test_single_linear_layer_normal_equations():
+    g = np.random.default_rng(10)
+    B, K, D = 12, 4, 3
+    X = g.standard_normal((B, K))
+    T = g.standard_normal((B, D))             # one class per sample: table row n
+    y = np.arange(B)
+    seg = _rand_segment([K, D], osg.RELU_HIDDEN_IDENTITY_LAST, osg.MSE_SIL, seed=2, lr=0.5)
+    out = seg.step(X, y, T, update=False)
+    R = X @ seg.W[0].T + seg.b[0] - T
+    assert np.allclose(out["dW"][0], 2.0 / (B * D) * R.T @ X, rtol=1e-12)
+    assert np.allclose(out["db"][0], 2.0 / (B * D) * R.sum(axis=0), rtol=1e-12)
+    for _ in range(6000):
+        seg.step(X, y, T)
+    Xa = np.hstack([X, np.ones((B, 1))])
+    sol = np.linalg.lstsq(Xa, T, rcond=None)[0]      # textbook least squares
+    assert np.allclose(seg.W[0], sol[:K].T, atol=1e-6) and np.allclose(seg.b[0], sol[K], atol=1e-6)
+
+
+def test_sgd_momentum_convention():
+    # 1 -> 1 identity layer with input 0: output = b, loss = (b - t)^2, dL/db = 2 (b - t)
+    # and dW = dZ * x = 0, so the bias follows the momentum recurrence alone.
+    X, T, y = np.array([[0.0]]), np.array([[1.0]]), np.array([0])
+    seg = osg.Segment([1, 1], osg.RELU_HIDDEN_IDENTITY_LAST, osg.MSE_SIL, lr=0.1, momentum=0.9)
+    # by hand: g1 = -2, v1 = -2, b1 = 0.2 ; g2 = -1.6, v2 = 0.9*(-2) - 1.6 = -3.4, b2 = 0.54
+    seg.step(X, y, T)
+    assert math.isclose(seg.b[0][0], 0.2, rel_tol=1e-15)
+    seg.step(X, y, T)
+    assert math.isclose(seg.b[0][0], 0.54, rel_tol=1e-14)
+    assert seg.W[0][0, 0] == 0.0
+    # momentum 0 is plain gradient descent: b <- b - lr * 2 (b - 1) = 0.8 b + 0.2
+    seg = osg.Segment([1, 1], osg.RELU_HIDDEN_IDENTITY_LAST, osg.MSE_SIL, lr=0.1, momentum=0.0)
+    for k in range(1, 6):
+        seg.step(X, y, T)
+        assert math.isclose(seg.b[0][0], 1.0 - 0.8 ** k, rel_tol=1e-13)
+    # constant gradient: cross-entropy with one class has p = 1, dZ = 0; instead use
+    # a frozen linear loss: two classes, logits (b0, b1) from x = 0, huge margin so
+    # the softmax saturates and dL/db = (1, -1)/1 * (p - onehot) ~ (+1, -1) constant
+    seg = osg.Segment([1, 2], osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT, lr=0.01, momentum=0.9)
+    seg.set_params(0, np.zeros((2, 1)), np.array([800.0, 0.0]))
+    for k in range(1, 8):
+        seg.step(X, np.array([1]), None)
+        drift = 0.01 * sum((1 - 0.9 ** i) / (1 - 0.9) for i in range(1, k + 1))   # lr g sum_i (1-mu^i)/(1-mu)
+        assert math.isclose(seg.b[0][0], 800.0 - drift, rel_tol=1e-13)
+        assert math.isclose(seg.b[0][1], drift, rel_tol=1e-12)
+
+
+def test_loss_decreases_on_separable_toy_set():
+    # 3 well separated classes; a 2-segment network trained the paper's way:
+    # left on synthetic labels (MSE), right on the left response (cross-entropy)
+    g = np.random.default_rng(12)
+    centres = np.array([[0.1, 0.1, 0.9, 0.1], [0.9, 0.1, 0.1, 0.5], [0.1, 0.9, 0.5, 0.9]])
+    y = datagen.balanced_classes(96, 3)
+    X = np.clip(centres[y] + 0.02 * g.standard_normal((96, 4)), 0, 1)
+    T = rng.make_synthetic_labels(7, 3, 8, rng.UNIFORM01, kappa=1.0).astype(np.float64)
+    # plain SGD with a small rate: the epoch-mean loss must fall monotonically
+    plain = _rand_segment([4, 16, 8], osg.RELU_ALL, osg.MSE_SIL, seed=5, lr=0.1, momentum=0.0)
+    epoch_loss = []
+    for ep in range(40):
+        tot = 0.0
+        for s in range(0, 96, 32):                          # no shuffling
+            tot += plain.step(X[s:s + 32], y[s:s + 32], T)["loss"]
+        epoch_loss.append(tot / 3)
+    assert all(b < a for a, b in zip(epoch_loss, epoch_loss[1:]))
+    assert epoch_loss[-1] < 0.3 * epoch_loss[0]
+    # the paper's optimiser setting (momentum 0.9) gets further in the same time
+    left = _rand_segment([4, 16, 8], osg.RELU_ALL, osg.MSE_SIL, seed=5, lr=0.05, momentum=0.9)
+    mom_loss = []
+    for ep in range(40):
+        tot = 0.0
+        for s in range(0, 96, 32):
+            tot += left.step(X[s:s + 32], y[s:s + 32], T)["loss"]
+        mom_loss.append(tot / 3)
+    assert mom_loss[-1] < 0.1 * mom_loss[0]
+    R = left.forward(X)                                     # stored left response
+    right = _rand_segment([8, 16, 3], osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT, seed=6, lr=0.1, momentum=0.9)
+    rl = []
+    for ep in range(40):
+        tot = 0.0
+        for s in range(0, 96, 32):
+            tot += right.step(R[s:s + 32], y[s:s + 32])["loss"]
+        rl.append(tot / 3)
+    assert rl[-1] < 0.2 * rl[0]
+    pred = right.forward(left.forward(X)).argmax(axis=1)    # joined partitions
+    assert (pred == y).mean() > 0.95
+
+
+# ---------------------------------------------------------------------------------
+# bf16 storage emulation
+# ---------------------------------------------------------------------------------
+def test_bf16_mode_is_exact_on_representable_values():
+    # small integers / powers of two: nothing is rounded, so both modes agree exactly
+    widths = [4, 4, 2]
+    g = np.random.default_rng(3)
+    Ws = [(g.integers(-2, 3, (4, 4)).astype(float), g.integers(-2, 3, 4).astype(float)),
+          (g.integers(-2, 3, (2, 4)).astype(float), g.integers(-2, 3, 2).astype(float))]
+    X = g.integers(0, 3, (4, 4)).astype(float)
+    T = g.integers(0, 3, (2, 2)).astype(float)
+    y = np.array([0, 1, 1, 0])
+    outs = []
+    for mode in ("fp32", "bf16"):
+        seg = osg.Segment(widths, osg.RELU_ALL, osg.MSE_SIL, mode=mode)
+        for l, (W, b) in enumerate(Ws):
+            seg.set_params(l, W, b)
+        outs.append(seg.step(X, y, T, update=False))
+    for l in range(2):
+        assert np.array_equal(outs[0]["dW"][l], outs[1]["dW"][l])
+        assert np.array_equal(outs[0]["A"][l + 1], outs[1]["A"][l + 1])
+    assert outs[0]["loss"] == outs[1]["loss"]
+
+
+def test_bf16_mode_rounds_at_storage_points_only():
+    widths = [16, 12, 8]
+    g = np.random.default_rng(4)
+    X = g.uniform(0, 1, (10, 16))
+    y = g.integers(0, 5, 10)
+    T = g.standard_normal((5, 8))
+    a = _rand_segment(widths, osg.RELU_ALL, osg.MSE_SIL, seed=1, mode="fp32")
+    b = _rand_segment(widths, osg.RELU_ALL, osg.MSE_SIL, seed=1, mode="bf16")
+    oa, ob = a.step(X, y, T, update=False), b.step(X, y, T, update=False)
+    for l in (1, 2):
+        A = ob["A"][l]
+        assert np.array_equal(A, rng.round_to_bf16(A.astype(np.float32)))       # on the bf16 grid
+        assert np.max(np.abs(A - oa["A"][l])) <= 2.0 ** -6 * np.max(np.abs(oa["A"][l]))
+    dz = ob["dZ"][2]
+    assert np.array_equal(dz, rng.round_to_bf16(dz.astype(np.float32)))
+    # dW is a float64 product of bf16-grid operands and is not itself rounded
+    assert np.allclose(ob["dW"][1], ob["dZ"][2].T @ ob["A"][1], rtol=1e-14)
+    assert not np.array_equal(ob["dW"][1], rng.round_to_bf16(ob["dW"][1].astype(np.float32)))
+    assert np.max(np.abs(ob["dW"][1] - oa["dW"][1])) <= 0.05 * np.max(np.abs(oa["dW"][1]))
