@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Throughput of the segment training step on one MI355X.
+
+    python bench.py [--config 4] [--steps K] [--warmup W] [--no-cpu] [--no-e2e]
+
+A "step" is one pass of the whole hot path -- forward, loss, backward confined to
+the segment, SGD update -- of EVERY segment of the chosen configuration over one
+batch of synthetic input that is already resident in HBM.  The default workload
+is the comparison configuration (784-16384-16384-16384 | 16384-16384-16384-1000,
+bf16 with float32 accumulation and master weights, batch 8192): the largest
+single-GPU workload, and the one the bf16-MFMA-peak target is stated on.
+
+Prints ONE JSON line.  `value` = samples/s through all segments' steps;
+`roofline` = the matrix-product kernel (all three products of the step run
+through it) priced against the dense bf16 MFMA peak, its duration measured live
+with HIP events on the launch stream; `cpu_baseline` = the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2403_11204_amd import api, datagen  # noqa: E402
+
+PEAK_TFLOPS = {api.BF16: 2516.6, api.F32: 157.3}     # dense MFMA peaks of MI355X
+MSE, CE = api.MSE_SIL, api.SOFTMAX_XENT
+ALL, LAST = api.RELU_ALL, api.RELU_HIDDEN_IDENTITY_LAST
+
+# name, dtype, batch, classes, samples, optimiser, segments: (widths, act, loss, label dist, label seed)
+CONFIGS = {
+    0: dict(name="tiny 784-128-64 | 64-64-47 fp32", dtype=api.F32, batch=64, classes=47, lr=0.01, mom=0.0, streams=False,
+            segs=[([784, 128, 64], ALL, MSE, api.UNIFORM_PM1, 7), ([64, 64, 47], LAST, CE, None, None)]),
+    1: dict(name="paper-shaped 784-1024-1024-512 | 512-1024-1024-47 fp32", dtype=api.F32, batch=256, classes=47, lr=0.01,
+            mom=0.9, streams=False,
+            segs=[([784, 1024, 1024, 512], ALL, MSE, api.NORMAL, 11), ([512, 1024, 1024, 47], LAST, CE, None, None)]),
+    2: dict(name="wide 784-4096-4096-2048 | 2048-4096-4096-47 bf16", dtype=api.BF16, batch=1024, classes=47, lr=0.01,
+            mom=0.9, streams=False,
+            segs=[([784, 4096, 4096, 2048], ALL, MSE, api.BINARY_PM1, 13), ([2048, 4096, 4096, 47], LAST, CE, None, None)]),
+    3: dict(name="deep 12x8192 in 4 segments on 4 streams bf16", dtype=api.BF16, batch=4096, classes=100, lr=0.01, mom=0.9,
+            streams=True,
+            segs=[([784, 8192, 8192, 8192], ALL, MSE, api.NORMAL, 21), ([8192, 8192, 8192, 8192], ALL, MSE, api.NORMAL, 22),
+                  ([8192, 8192, 8192, 8192], ALL, MSE, api.NORMAL, 23), ([8192, 8192, 8192, 100], LAST, CE, None, None)]),
+    4: dict(name="comparison 784-16384-16384-16384 | 16384-16384-16384-1000 bf16", dtype=api.BF16, batch=8192, classes=1000,
+            lr=0.01, mom=0.9, streams=False,
+            segs=[([784, 16384, 16384, 16384], ALL, MSE, api.UNIFORM_PM1, 31),
+                  ([16384, 16384, 16384, 1000], LAST, CE, None, None)]),
+}
+E2E_WIDTHS = [784, 16384, 16384, 16384, 16384, 16384, 1000]
+
+
+def gemm_flops_per_sample(widths):
+    P = sum(widths[i] * widths[i + 1] for i in range(len(widths) - 1))
+    return 6 * P - 2 * widths[0] * widths[1]
+
+
+def build_segments(cfg, n_batches):
+    """Handles, label tables and per-segment inputs for n_batches resident batches."""
+    dt, B, classes = cfg["dtype"], cfg["batch"], cfg["classes"]
+    tdt = torch.bfloat16 if dt == api.BF16 else torch.float32
+    ys, X0 = [], []
+    for i in range(n_batches):
+        X, y = datagen.class_mean_inputs(B, classes, dim=784, seed=1, first=i * B)
+        X0.append(torch.from_numpy(X).cuda().to(tdt).contiguous())
+        ys.append(torch.from_numpy(y).cuda())
+    segs, inputs = [], []
+    prev_table = None
+    for si, (widths, act, loss, dist, seed) in enumerate(cfg["segs"]):
+        seg = api.Segment(widths, act, loss, max_batch=B, dtype=dt, lr=cfg["lr"], momentum=cfg["mom"])
+        seg.init(100 + si)
+        if si == 0:
+            inputs.append(X0)
+        else:   # an interior/final segment sees the previous cut's label of the class plus noise (sigma 0.05)
+            inputs.append([api.make_segment_inputs(5 + si, prev_table, ys[i], i * B, 0.05, dt) for i in range(n_batches)])
+        if loss == MSE:
+            prev_table = api.make_synthetic_labels(seed, classes, widths[-1], dist, 1.0, api.F32)
+            seg.set_labels(prev_table)
+        segs.append(seg)
+    return segs, inputs, ys
+
+
+def run_steps(segs, inputs, ys, streams, k0, k):
+    for it in range(k0, k0 + k):
+        bi = it % len(ys)
+        if streams:
+            for seg, xin, st in zip(segs, inputs, streams):
+                with torch.cuda.stream(st):
+                    seg.step(xin[bi], ys[bi], want_loss=True)
+        else:
+            for seg, xin in zip(segs, inputs):
+                seg.step(xin[bi], ys[bi], want_loss=True)
+
+
+def time_workload(segs, inputs, ys, use_streams, steps, warmup, profile=True):
+    """Returns (wall ms/step, event ms/step, per-segment (gemm ms, launches, flops))."""
+    streams = [torch.cuda.Stream() for _ in segs] if use_streams else None
+    cur = torch.cuda.current_stream()
+    if streams:
+        for st in streams:
+            st.wait_stream(cur)
+    run_steps(segs, inputs, ys, streams, 0, warmup)
+    torch.cuda.synchronize()
+    if profile:
+        for s in segs:
+            s.profile_enable(steps * 3 * s.L + 8)     # event pairs created before the clock starts
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    run_steps(segs, inputs, ys, streams, warmup, steps)
+    if streams:
+        for st in streams:
+            cur.wait_stream(st)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    prof = [s.profile_read() for s in segs] if profile else None
+    for s in segs:
+        s.profile_enable(False)
+    return wall_ms / steps, ev0.elapsed_time(ev1) / steps, prof
+
+
+def cpu_baseline(cfg, rows, max_seconds=60.0):
+    """The CPU oracle, as it stands, on `rows` rows of the same workload (all segments)."""
+    from oracle import rng as orng
+    from oracle import segment as osg
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    mode = "bf16" if cfg["dtype"] == api.BF16 else "fp32"
+    classes = cfg["classes"]
+    X, y = datagen.class_mean_inputs(rows, classes, dim=784, seed=1)
+    total, prev = 0.0, None
+    for si, (widths, act, loss, dist, seed) in enumerate(cfg["segs"]):
+        o = osg.Segment(widths, act, loss, lr=cfg["lr"], momentum=cfg["mom"], mode=mode)
+        for l in range(o.L):
+            W, b = orng.init_weights(100 + si, l, widths[l + 1], widths[l])
+            o.set_params(l, W, b)
+        xin = X if si == 0 else orng.make_segment_inputs(5 + si, prev, y, 0, 0.05)
+        table = None
+        if loss == MSE:
+            table = orng.make_synthetic_labels(seed, classes, widths[-1], dist, 1.0)
+            prev = table
+        t0 = time.perf_counter()
+        o.step(xin, y, table)
+        total += time.perf_counter() - t0
+        del o
+    return {"value": rows / total, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": "one step of every segment at full widths on %d rows (%.1f s of CPU time)" % (rows, total)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=4, choices=sorted(CONFIGS))
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-e2e", action="store_true", help="skip the end-to-end backprop comparison (config 4)")
+    ap.add_argument("--cpu-rows", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (segments are independent jobs; no collectives exist): use --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    cfg = CONFIGS[args.config]
+    big = args.config >= 3
+    steps = args.steps if args.steps is not None else (20 if big else 200)
+    warmup = args.warmup if args.warmup is not None else (3 if big else 20)
+    dt, B = cfg["dtype"], cfg["batch"]
+
+    torch.cuda.reset_peak_memory_stats()
+    segs, inputs, ys = build_segments(cfg, n_batches=2 if big else 8)
+    torch.cuda.synchronize()
+    wall_ms, ev_ms, prof = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup)
+    ms = max(wall_ms, ev_ms) if not cfg["streams"] else wall_ms
+    flops_step = sum(gemm_flops_per_sample(s[0]) for s in cfg["segs"]) * B
+    peak = PEAK_TFLOPS[dt]
+    gemm_ms = sum(p[0] for p in prof)
+    gemm_n = sum(p[1] for p in prof)
+    gemm_fl = sum(p[2] for p in prof)
+    achieved = gemm_fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    seg_bytes = [(s.param_bytes, s.workspace_bytes) for s in segs]
+    out = {
+        "metric": "segment_train_samples_per_s", "value": B / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if dt == api.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": cfg["name"], "global_batch": B, "classes": cfg["classes"],
+                   "segments": [s[0] for s in cfg["segs"]], "optimizer": "sgd lr %g momentum %g" % (cfg["lr"], cfg["mom"]),
+                   "concurrent_streams": len(segs) if cfg["streams"] else 1},
+        "step_tflops": flops_step / (ms * 1e-3) / 1e12,
+        "step_frac_of_mfma_peak": flops_step / (ms * 1e-3) / 1e12 / peak,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": None, "kernel": "gemm_nt_kernel", "launches": gemm_n,
+                     "avg_launch_ms": gemm_ms / max(gemm_n, 1), "flops_per_launch": gemm_fl / max(gemm_n, 1)},
+        "segment_bytes": [{"params": p, "workspace": w} for p, w in seg_bytes],
+        "peak_hbm_bytes_torch": int(torch.cuda.max_memory_allocated()),
+    }
+    if not cfg["streams"]:
+        out["per_segment_gemm_ms"] = [p[0] / steps for p in prof]
+
+    if args.config == 4 and not args.no_e2e:
+        # conventional end-to-end backprop through all six layers on the same GPU, same library
+        del segs, inputs
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats()
+        e2e = api.Segment(E2E_WIDTHS, LAST, CE, max_batch=B, dtype=dt, lr=cfg["lr"], momentum=cfg["mom"])
+        e2e.init(200)
+        X0 = []
+        for i in range(2):
+            X, _ = datagen.class_mean_inputs(B, cfg["classes"], dim=784, seed=1, first=i * B)
+            X0.append(torch.from_numpy(X).cuda().to(torch.bfloat16).contiguous())
+        ks = max(3, steps // 2)
+        w_ms, e_ms, p = time_workload([e2e], [X0], ys, False, ks, 2)
+        m = max(w_ms, e_ms)
+        fl = gemm_flops_per_sample(E2E_WIDTHS) * B
+        out["end_to_end_baseline"] = {
+            "widths": E2E_WIDTHS, "ms_per_step": m, "samples_per_s": B / (m * 1e-3), "tflops": fl / (m * 1e-3) / 1e12,
+            "params_bytes": e2e.param_bytes, "workspace_bytes": e2e.workspace_bytes,
+            "peak_hbm_bytes_torch": int(torch.cuda.max_memory_allocated()),
+            "segmentwise_peak_bytes": max(p_ + w_ for p_, w_ in seg_bytes),
+            "segmentwise_ms_per_step": ms}
+        del e2e
+        torch.cuda.empty_cache()
+
+    if not args.no_cpu:
+        rows = args.cpu_rows or {0: 64, 1: 256, 2: 256, 3: 16, 4: 8}[args.config]
+        out["cpu_baseline"] = cpu_baseline(cfg, rows)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,159 @@
+/*
+ * slp -- segment-wise training with synthetic intermediate labels on one AMD
+ * MI355X (gfx950).  C ABI of the hot path of "Partitioned Neural Network
+ * Training via Synthetic Intermediate Labels" (arXiv 2403.11204): the independent
+ * training step of one network segment.
+ *
+ * Conventions
+ *   - every function returns SLP_OK (0) or a negative slp_status; nothing throws
+ *     across this boundary; slp_last_error() gives a thread-local message;
+ *   - "device" pointers are HIP device addresses on the current device, "host"
+ *     pointers are ordinary host memory; the library allocates NO device memory:
+ *     every device byte it uses is handed in by the caller (slp_segment_bind);
+ *   - slp_stream is a hipStream_t passed as void* (NULL = the default stream);
+ *     calls that take a stream are asynchronous on it unless stated otherwise;
+ *   - matrices are row-major; a weight matrix is [out][in] as in the paper's
+ *     parameter count (in+1)*out (Sec. 3);
+ *   - a label table is stored [classes][dim]: row j is the synthetic intermediate
+ *     label of class j (the paper's SIL is the transpose, one column per class).
+ *   - argument validation happens on the host before any device work is queued.
+ */
+#ifndef SLP_H
+#define SLP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct slp_segment slp_segment;
+typedef void* slp_stream;
+
+typedef enum {
+  SLP_OK = 0,
+  SLP_ERR_ARG = -1,    /* null pointer, unknown enum value, non-positive size */
+  SLP_ERR_SHAPE = -2,  /* sizes that do not fit each other or the handle's limits */
+  SLP_ERR_ALLOC = -3,  /* a caller-provided buffer is too small or misaligned */
+  SLP_ERR_DEVICE = -4, /* the HIP runtime reported an error */
+  SLP_ERR_STATE = -5   /* call made before the state it needs exists */
+} slp_status;
+
+/* label distributions: Eq. 1 of the paper is SLP_UNIFORM01 (kappa * U[0,1)) */
+typedef enum { SLP_UNIFORM01 = 0, SLP_UNIFORM_PM1 = 1, SLP_NORMAL = 2, SLP_BINARY_PM1 = 3 } slp_dist;
+typedef enum { SLP_F32 = 0, SLP_BF16 = 1 } slp_dtype;
+/* Sec. 3: ReLU after every layer except the network's last one.  A non-final
+ * segment ends at a cut and keeps its ReLU (SLP_RELU_ALL); the final segment
+ * ends in the identity (SLP_RELU_HIDDEN_IDENTITY_LAST). */
+typedef enum { SLP_RELU_ALL = 0, SLP_RELU_HIDDEN_IDENTITY_LAST = 1 } slp_act;
+/* Sec. 2: a non-final segment regresses on the synthetic label of the sample's
+ * class (mean squared error over batch x width); the final segment is trained on
+ * the true classes (softmax cross-entropy, mean over the batch). */
+typedef enum { SLP_MSE_SIL = 0, SLP_SOFTMAX_XENT = 1 } slp_loss;
+
+typedef struct {
+  int dtype;      /* slp_dtype: SLP_F32 = everything float32; SLP_BF16 = bf16 weights copy,
+                     activations and dZ with float32 accumulation, float32 master weights,
+                     gradients, momentum and biases */
+  int max_batch;  /* largest batch a step or forward call may pass */
+  float lr;       /* SGD learning rate (Sec. 3 uses 0.01) */
+  float momentum; /* SGD momentum (Sec. 3 uses 0.9); 0 = plain SGD */
+} slp_opts;
+
+const char* slp_last_error(void);
+
+/* ---- synthetic intermediate labels (Sec. 2, Eq. 1) --------------------------------
+ * Writes T[classes][dim] (dense, row-major, dtype dt) to the caller-owned device
+ * buffer `table`.  Entry (j,i) is a pure function of (seed, j, i, dist, kappa):
+ * Philox4x32-10 with key = seed and counter (i, j, 0, 0), then a fixed float32
+ * transform; kappa only scales SLP_UNIFORM01.  Bit-exact against the CPU
+ * definition.  A bf16 table is the float32 value rounded to nearest even. */
+int slp_make_synthetic_labels(uint64_t seed, int classes, int dim, int dist, float kappa,
+                              void* table /*device*/, int dt, slp_stream stream);
+
+/* ---- inputs of an interior segment in the simultaneous variant (Sec. 2, the
+ * variant that trains every partition at once, where an interior partition takes
+ * synthetic labels as its inputs as well as its targets) ----------------------------
+ * out[n][i] = table[y[n]][i] + sigma * N(0,1), noise counter = global sample index
+ * first_sample + n (Philox stream 2).  table: float32 [classes][dim] device;
+ * y: int32 [batch] device, each in [0,classes) (clamped into range on the device);
+ * out: [batch][dim] of dtype dt, device, caller-owned. */
+int slp_make_segment_inputs(uint64_t seed, const float* table /*device*/, int classes, const int32_t* y /*device*/,
+                            int64_t first_sample, int batch, int dim, float sigma,
+                            void* out /*device*/, int dt, slp_stream stream);
+
+/* ---- segment handle (Sec. 2: one partition; Sec. 2.1: its own hyper-parameters) ----
+ * widths[0..n_widths-1] = input width then the width of every layer, n_widths >= 2.
+ * The handle is host memory owned by the library until slp_segment_destroy. */
+int slp_segment_create(const int* widths /*host*/, int n_widths, int act, int loss, const slp_opts* opts /*host*/,
+                       slp_segment** out);
+void slp_segment_destroy(slp_segment* seg);
+
+/* Bytes of device memory the segment needs: parameters + optimiser state +
+ * gradients ("params"), and activations / per-step temporaries ("workspace"). */
+size_t slp_segment_param_bytes(const slp_segment* seg);
+size_t slp_segment_workspace_bytes(const slp_segment* seg);
+
+/* Hands the two caller-owned device buffers (256-byte aligned, at least the sizes
+ * above) to the segment and zero-fills them on `stream`.  They must outlive every
+ * later call on the handle; the library never frees them. */
+int slp_segment_bind(slp_segment* seg, void* params /*device*/, size_t params_bytes, void* workspace /*device*/,
+                     size_t workspace_bytes, slp_stream stream);
+
+/* Initial parameters U(-1/sqrt(fan_in), 1/sqrt(fan_in)) for weights and biases (the
+ * default of the framework named in Sec. 2), drawn from Philox stream 1 with
+ * counter (in, out, 1, layer), bias at in = fan_in; momentum is reset to zero. */
+int slp_segment_init(slp_segment* seg, uint64_t seed, slp_stream stream);
+
+/* Parameter / gradient / momentum exchange, always as dense float32 W[out][in] and
+ * b[out] whatever the internal layout; layer in [0, n_widths-2]; on_device selects
+ * host or device pointers for W and b; either pointer may be NULL to skip it.  The
+ * calls synchronise `stream` before returning when a host pointer is involved.
+ * set_params also rebuilds the derived weight copies and leaves momentum alone. */
+int slp_segment_set_params(slp_segment* seg, int layer, const float* W, const float* b, int on_device, slp_stream stream);
+int slp_segment_get_params(slp_segment* seg, int layer, float* W, float* b, int on_device, slp_stream stream);
+int slp_segment_get_grads(slp_segment* seg, int layer, float* dW, float* db, int on_device, slp_stream stream);
+int slp_segment_get_momentum(slp_segment* seg, int layer, float* vW, float* vb, int on_device, slp_stream stream);
+/* Copies the stored activation A_layer (layer 0 = the ingested input, layer L =
+ * the segment's output) of the last step, rows [0,batch), to out[batch][width],
+ * dense, in the handle's dtype (device pointer). kind 0 = activation, 1 = dZ (layers 1..L). */
+int slp_segment_get_activation(slp_segment* seg, int layer, int kind, int batch, void* out /*device*/, slp_stream stream);
+
+int slp_segment_set_lr(slp_segment* seg, float lr, float momentum);
+
+/* Label table for a SLP_MSE_SIL segment: float32 [classes][dim] on the device with
+ * dim == the segment's last width; caller-owned, must outlive the steps. */
+int slp_segment_set_labels(slp_segment* seg, const float* table /*device*/, int classes, int dim);
+
+/* ---- the training step (Sec. 2: first and second training phase; Sec. 3:
+ * optimiser and activations) -------------------------------------------------------
+ * One pass of forward, loss, backward confined to the segment, and the SGD update
+ * for the batch X[batch][widths[0]] (dense, handle dtype, device) with class ids
+ * targets[batch] (int32, device).  For SLP_MSE_SIL the ids select rows of the bound
+ * label table; for SLP_SOFTMAX_XENT they are the classes (< last width).  Ids are
+ * clamped into range on the device.  If loss_out is not NULL the mean loss of the
+ * batch (before the update) is written there (float32, device).  No host
+ * synchronisation; X and targets are only read. */
+int slp_segment_step(slp_segment* seg, const void* X /*device*/, const int32_t* targets /*device*/, int batch,
+                     float* loss_out /*device, may be NULL*/, slp_stream stream);
+
+/* Forward only (Sec. 2: the stored response of the left partition; joining the
+ * partitions): out[batch][last width], dense, handle dtype, device.  Parameters
+ * are not changed; the activation workspace is overwritten. */
+int slp_segment_forward(slp_segment* seg, const void* X /*device*/, int batch, void* out /*device*/, slp_stream stream);
+
+/* ---- measurement hooks -------------------------------------------------------------
+ * When enabled, every matrix-product launch of the segment is bracketed by HIP
+ * events on its stream.  slp_segment_profile_read synchronises the recorded events,
+ * returns the accumulated device time of those launches (milliseconds), their count
+ * and their algorithmic FLOPs (2*M*N*K with unpadded sizes), then clears the log.
+ * on > 1 additionally creates `on` event pairs up front so that none has to be
+ * created between timed launches. */
+int slp_segment_profile_enable(slp_segment* seg, int on);
+int slp_segment_profile_read(slp_segment* seg, double* gemm_ms, int64_t* gemm_launches, double* gemm_flops);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLP_H */

@@ -1,0 +1,196 @@
+"""Python names for the C ABI in include/slp.h -- argument marshalling only.
+
+Every function here packs its arguments, calls the library entry point of the
+same name and raises ``SlpError`` on a non-zero status.  Tensors are torch CUDA
+tensors used as raw device memory; the stream passed to the library is torch's
+current stream, so ordinary torch stream semantics apply.
+"""
+
+import ctypes
+import os
+
+import torch
+
+UNIFORM01, UNIFORM_PM1, NORMAL, BINARY_PM1 = 0, 1, 2, 3
+F32, BF16 = 0, 1
+RELU_ALL, RELU_HIDDEN_IDENTITY_LAST = 0, 1
+MSE_SIL, SOFTMAX_XENT = 0, 1
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libslp.so")
+_lib = None
+
+
+class SlpError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__("slp error %d: %s" % (code, message))
+        self.code = code
+
+
+class _Opts(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int), ("max_batch", ctypes.c_int), ("lr", ctypes.c_float), ("momentum", ctypes.c_float)]
+
+
+def lib():
+    """Loads libslp.so once.  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError("%s is missing: build it with `python -m paper_2403_11204_amd.build` "
+                           "(there is no fallback path)" % _LIB_PATH)
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, u64, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64, ctypes.c_float, ctypes.c_size_t
+    sig = {
+        "slp_last_error": (ctypes.c_char_p, []),
+        "slp_make_synthetic_labels": (i32, [u64, i32, i32, i32, f32, vp, i32, vp]),
+        "slp_make_segment_inputs": (i32, [u64, vp, i32, vp, i64, i32, i32, f32, vp, i32, vp]),
+        "slp_segment_create": (i32, [ctypes.POINTER(i32), i32, i32, i32, ctypes.POINTER(_Opts), ctypes.POINTER(vp)]),
+        "slp_segment_destroy": (None, [vp]),
+        "slp_segment_param_bytes": (sz, [vp]),
+        "slp_segment_workspace_bytes": (sz, [vp]),
+        "slp_segment_bind": (i32, [vp, vp, sz, vp, sz, vp]),
+        "slp_segment_init": (i32, [vp, u64, vp]),
+        "slp_segment_set_params": (i32, [vp, i32, vp, vp, i32, vp]),
+        "slp_segment_get_params": (i32, [vp, i32, vp, vp, i32, vp]),
+        "slp_segment_get_grads": (i32, [vp, i32, vp, vp, i32, vp]),
+        "slp_segment_get_momentum": (i32, [vp, i32, vp, vp, i32, vp]),
+        "slp_segment_get_activation": (i32, [vp, i32, i32, i32, vp, vp]),
+        "slp_segment_set_lr": (i32, [vp, f32, f32]),
+        "slp_segment_set_labels": (i32, [vp, vp, i32, i32]),
+        "slp_segment_step": (i32, [vp, vp, vp, i32, vp, vp]),
+        "slp_segment_forward": (i32, [vp, vp, i32, vp, vp]),
+        "slp_segment_profile_enable": (i32, [vp, i32]),
+        "slp_segment_profile_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+EXPORTS = ["slp_last_error", "slp_make_synthetic_labels", "slp_make_segment_inputs", "slp_segment_create",
+           "slp_segment_destroy", "slp_segment_param_bytes", "slp_segment_workspace_bytes", "slp_segment_bind",
+           "slp_segment_init", "slp_segment_set_params", "slp_segment_get_params", "slp_segment_get_grads",
+           "slp_segment_get_momentum", "slp_segment_get_activation", "slp_segment_set_lr", "slp_segment_set_labels",
+           "slp_segment_step", "slp_segment_forward", "slp_segment_profile_enable", "slp_segment_profile_read"]
+
+
+def _check(code):
+    if code != 0:
+        raise SlpError(code, lib().slp_last_error().decode())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _torch_dtype(dt):
+    return torch.bfloat16 if dt == BF16 else torch.float32
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def make_synthetic_labels(seed, classes, dim, dist, kappa=1.0, dtype=F32, device="cuda"):
+    """slp_make_synthetic_labels: table[classes, dim] on the device."""
+    out = torch.empty((classes, dim), dtype=_torch_dtype(dtype), device=device)
+    _check(lib().slp_make_synthetic_labels(seed, classes, dim, dist, kappa, _ptr(out), dtype, _stream()))
+    return out
+
+
+def make_segment_inputs(seed, table, y, first_sample, sigma, dtype=F32):
+    """slp_make_segment_inputs: out[n] = table[y[n]] + sigma * N(0,1)."""
+    assert table.dtype == torch.float32 and table.is_contiguous() and y.dtype == torch.int32
+    out = torch.empty((y.numel(), table.shape[1]), dtype=_torch_dtype(dtype), device=table.device)
+    _check(lib().slp_make_segment_inputs(seed, _ptr(table), table.shape[0], _ptr(y), first_sample, y.numel(),
+                                         table.shape[1], sigma, _ptr(out), dtype, _stream()))
+    return out
+
+
+class Segment:
+    """One network segment: owns the handle and the two torch buffers bound to it."""
+
+    def __init__(self, widths, act, loss, max_batch, dtype=F32, lr=0.01, momentum=0.9, device="cuda"):
+        self.widths, self.act, self.loss, self.dtype, self.max_batch = list(widths), act, loss, dtype, max_batch
+        self.L = len(widths) - 1
+        self.device = torch.device(device)
+        arr = (ctypes.c_int * len(widths))(*widths)
+        opts = _Opts(dtype, max_batch, lr, momentum)
+        h = ctypes.c_void_p()
+        self._h = None
+        _check(lib().slp_segment_create(arr, len(widths), act, loss, ctypes.byref(opts), ctypes.byref(h)))
+        self._h = h
+        self.param_bytes = lib().slp_segment_param_bytes(h)
+        self.workspace_bytes = lib().slp_segment_workspace_bytes(h)
+        self._params = torch.empty(self.param_bytes, dtype=torch.uint8, device=self.device)
+        self._work = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+        _check(lib().slp_segment_bind(h, _ptr(self._params), self.param_bytes, _ptr(self._work), self.workspace_bytes, _stream()))
+        self._table = None
+        self._loss = torch.zeros(1, dtype=torch.float32, device=self.device)
+
+    def __del__(self):
+        if getattr(self, "_h", None) is not None and _lib is not None:
+            _lib.slp_segment_destroy(self._h)
+            self._h = None
+
+    def init(self, seed):
+        _check(lib().slp_segment_init(self._h, seed, _stream()))
+
+    def set_lr(self, lr, momentum):
+        _check(lib().slp_segment_set_lr(self._h, lr, momentum))
+
+    def set_labels(self, table):
+        assert table.dtype == torch.float32 and table.is_contiguous()
+        self._table = table     # keep it alive: the library only borrows it
+        _check(lib().slp_segment_set_labels(self._h, _ptr(table), table.shape[0], table.shape[1]))
+
+    def set_params(self, layer, W, b):
+        W = None if W is None else W.to(torch.float32).contiguous()
+        b = None if b is None else b.to(torch.float32).contiguous()
+        on_dev = int((W if W is not None else b).is_cuda)
+        _check(lib().slp_segment_set_params(self._h, layer, _ptr(W), _ptr(b), on_dev, _stream()))
+
+    def _get(self, fn, layer):
+        W = torch.empty((self.widths[layer + 1], self.widths[layer]), dtype=torch.float32, device=self.device)
+        b = torch.empty((self.widths[layer + 1],), dtype=torch.float32, device=self.device)
+        _check(fn(self._h, layer, _ptr(W), _ptr(b), 1, _stream()))
+        return W, b
+
+    def get_params(self, layer):
+        return self._get(lib().slp_segment_get_params, layer)
+
+    def get_grads(self, layer):
+        return self._get(lib().slp_segment_get_grads, layer)
+
+    def get_momentum(self, layer):
+        return self._get(lib().slp_segment_get_momentum, layer)
+
+    def get_activation(self, layer, batch, kind=0):
+        out = torch.empty((batch, self.widths[layer]), dtype=_torch_dtype(self.dtype), device=self.device)
+        _check(lib().slp_segment_get_activation(self._h, layer, kind, batch, _ptr(out), _stream()))
+        return out
+
+    def step(self, X, targets, want_loss=True):
+        """slp_segment_step; returns the device scalar holding the batch loss."""
+        assert X.is_cuda and X.is_contiguous() and X.dtype == _torch_dtype(self.dtype) and X.shape[1] == self.widths[0]
+        assert targets.dtype == torch.int32 and targets.numel() == X.shape[0]
+        _check(lib().slp_segment_step(self._h, _ptr(X), _ptr(targets), X.shape[0], _ptr(self._loss) if want_loss else None,
+                                      _stream()))
+        return self._loss
+
+    def forward(self, X, out=None):
+        assert X.is_cuda and X.is_contiguous() and X.dtype == _torch_dtype(self.dtype) and X.shape[1] == self.widths[0]
+        if out is None:
+            out = torch.empty((X.shape[0], self.widths[-1]), dtype=X.dtype, device=X.device)
+        _check(lib().slp_segment_forward(self._h, _ptr(X), X.shape[0], _ptr(out), _stream()))
+        return out
+
+    def profile_enable(self, on=True):
+        _check(lib().slp_segment_profile_enable(self._h, int(on)))
+
+    def profile_read(self):
+        ms, n, fl = ctypes.c_double(), ctypes.c_int64(), ctypes.c_double()
+        _check(lib().slp_segment_profile_read(self._h, ctypes.byref(ms), ctypes.byref(n), ctypes.byref(fl)))
+        return ms.value, n.value, fl.value

@@ -1,0 +1,496 @@
+// C ABI of the segment-training library (see include/slp.h for the contract).
+// Host code only: argument validation, the device-memory carve-up of the two
+// caller-provided buffers, and the launch sequence of one training step
+// (paper Sec. 2: a segment is trained on its own inputs and targets, nothing
+// flows to or from another segment).
+#include "../../include/slp.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "slp_kernels.h"
+
+using namespace slp;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                             \
+  do {                                                                                            \
+    hipError_t e__ = (expr);                                                                      \
+    if (e__ != hipSuccess) return fail(SLP_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layer {
+  int K, N;        // fan-in, fan-out
+  int ldk, ldn;    // padded leading dimensions of [N][ldk] and [K][ldn] matrices
+  // offsets into the parameter buffer
+  size_t oW32, ovW, odW, ob, ovb, odb, oW16, oWT;
+  // bound pointers
+  float *W32, *vW, *dW, *b, *vb, *db;
+  void *Wop;       // forward operand: W16 (bf16 mode) or W32
+  void *W16;       // bf16 copy or null
+  void *WT;        // [K][ldn] transposed copy for the data gradient, null for the first layer
+};
+
+struct ProfRec { hipEvent_t a, b; double flops; };
+
+}  // namespace
+
+struct slp_segment {
+  int L, act, loss, dtype, max_batch, ldb;   // ldb: leading dimension of batch-contiguous buffers
+  float lr, mu;
+  std::vector<int> widths, ldw;              // ldw[l] = padded width l
+  std::vector<Layer> layers;
+  size_t param_bytes, work_bytes;
+  // workspace offsets / pointers, index = layer 0..L
+  std::vector<size_t> oA, oAT, odZ, odZT;
+  std::vector<void*> A, AT, dZ, dZT;
+  size_t oPartials, oLoss;
+  int n_partials;
+  float *partials, *loss_dev;
+  bool bound, have_params;
+  const float* table;
+  int classes;
+  int last_batch;
+  bool prof;
+  std::vector<ProfRec> prof_log;
+  std::vector<hipEvent_t> ev_pool;
+};
+
+namespace {
+
+int esize(const slp_segment* s) { return s->dtype == SLP_BF16 ? 2 : 4; }
+bool relu_on(const slp_segment* s, int l) { return l < s->L || s->act == SLP_RELU_ALL; }
+
+hipEvent_t get_event(slp_segment* s) {
+  if (!s->ev_pool.empty()) {
+    hipEvent_t e = s->ev_pool.back();
+    s->ev_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+int run_gemm(slp_segment* s, int epi, const GemmArgs& g, hipStream_t st) {
+  ProfRec rec{nullptr, nullptr, 2.0 * g.M * (double)g.N * g.K};
+  if (s->prof) {
+    rec.a = get_event(s);
+    rec.b = get_event(s);
+    if (!rec.a || !rec.b) return fail(SLP_ERR_DEVICE, "hipEventCreate failed");
+    HIP_TRY(hipEventRecord(rec.a, st));
+  }
+  HIP_TRY(launch_gemm(s->dtype, epi, g, st));
+  if (s->prof) {
+    HIP_TRY(hipEventRecord(rec.b, st));
+    s->prof_log.push_back(rec);
+  }
+  return SLP_OK;
+}
+
+int check_seg(const slp_segment* s, bool need_bound, bool need_params) {
+  if (!s) return fail(SLP_ERR_ARG, "segment handle is NULL");
+  if (need_bound && !s->bound) return fail(SLP_ERR_STATE, "segment has no device buffers: call slp_segment_bind first");
+  if (need_params && !s->have_params)
+    return fail(SLP_ERR_STATE, "segment has no parameters: call slp_segment_init or slp_segment_set_params first");
+  return SLP_OK;
+}
+
+// X[batch][w0] -> A[0] (padded rows) and, for training, its transpose
+int ingest(slp_segment* s, const void* X, int batch, bool with_transpose, hipStream_t st) {
+  HIP_TRY(launch_copy_transpose(s->dtype, X, s->widths[0], batch, s->widths[0], s->A[0], s->ldw[0],
+                                with_transpose ? s->AT[0] : nullptr, s->ldb, 1, st));
+  return SLP_OK;
+}
+
+int forward_layers(slp_segment* s, int batch, bool training, hipStream_t st) {
+  for (int l = 1; l <= s->L; ++l) {
+    const Layer& ly = s->layers[l - 1];
+    GemmArgs g{};
+    g.A = s->A[l - 1]; g.lda = s->ldw[l - 1];
+    g.B = ly.Wop;      g.ldb = ly.ldk;
+    g.M = batch; g.N = ly.N; g.K = ly.K;
+    g.C = s->A[l]; g.ldc = s->ldw[l];
+    g.CT = (training && l < s->L) ? s->AT[l] : nullptr; g.ldct = s->ldb;
+    g.bias = ly.b; g.relu = relu_on(s, l) ? 1 : 0;
+    int rc = run_gemm(s, EPI_FWD, g, st);
+    if (rc) return rc;
+  }
+  return SLP_OK;
+}
+
+int refresh_copies(slp_segment* s, int layer, hipStream_t st) {
+  Layer& ly = s->layers[layer];
+  if (!ly.W16 && !ly.WT) return SLP_OK;
+  HIP_TRY(launch_sgd_update(s->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, 0.0f, 0.0f, 1, st));
+  return SLP_OK;
+}
+
+int copy_matrix(float* dense, float* padded, int rows, int cols, int ld, bool to_padded, int on_device, hipStream_t st) {
+  const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : (to_padded ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost);
+  if (to_padded)
+    HIP_TRY(hipMemcpy2DAsync(padded, (size_t)ld * 4, dense, (size_t)cols * 4, (size_t)cols * 4, rows, kind, st));
+  else
+    HIP_TRY(hipMemcpy2DAsync(dense, (size_t)cols * 4, padded, (size_t)ld * 4, (size_t)cols * 4, rows, kind, st));
+  return SLP_OK;
+}
+
+int exchange(slp_segment* s, int layer, float* W, float* b, int which, bool set, int on_device, hipStream_t st) {
+  int rc = check_seg(s, true, !set);
+  if (rc) return rc;
+  if (layer < 0 || layer >= s->L) return fail(SLP_ERR_ARG, "layer %d out of range [0,%d)", layer, s->L);
+  Layer& ly = s->layers[layer];
+  float* mats[3] = {ly.W32, ly.dW, ly.vW};
+  float* vecs[3] = {ly.b, ly.db, ly.vb};
+  if (W) {
+    rc = copy_matrix(W, mats[which], ly.N, ly.K, ly.ldk, set, on_device, st);
+    if (rc) return rc;
+  }
+  if (b) {
+    const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : (set ? hipMemcpyHostToDevice : hipMemcpyDeviceToHost);
+    if (set) HIP_TRY(hipMemcpyAsync(vecs[which], b, (size_t)ly.N * 4, kind, st));
+    else HIP_TRY(hipMemcpyAsync(b, vecs[which], (size_t)ly.N * 4, kind, st));
+  }
+  if (set && W) {
+    rc = refresh_copies(s, layer, st);
+    if (rc) return rc;
+  }
+  if (!on_device) HIP_TRY(hipStreamSynchronize(st));
+  return SLP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* slp_last_error(void) { return g_err; }
+
+int slp_make_synthetic_labels(uint64_t seed, int classes, int dim, int dist, float kappa, void* table, int dt,
+                              slp_stream stream) {
+  if (!table) return fail(SLP_ERR_ARG, "table is NULL");
+  if (classes <= 0 || dim <= 0) return fail(SLP_ERR_ARG, "classes and dim must be positive (got %d, %d)", classes, dim);
+  if (dist < SLP_UNIFORM01 || dist > SLP_BINARY_PM1) return fail(SLP_ERR_ARG, "unknown distribution %d", dist);
+  if (dt != SLP_F32 && dt != SLP_BF16) return fail(SLP_ERR_ARG, "unknown dtype %d", dt);
+  HIP_TRY(launch_make_labels(seed, classes, dim, dist, kappa, table, dt, (hipStream_t)stream));
+  return SLP_OK;
+}
+
+int slp_make_segment_inputs(uint64_t seed, const float* table, int classes, const int32_t* y, int64_t first_sample,
+                            int batch, int dim, float sigma, void* out, int dt, slp_stream stream) {
+  if (!table || !y || !out) return fail(SLP_ERR_ARG, "table, y and out must not be NULL");
+  if (classes <= 0 || dim <= 0 || batch <= 0 || first_sample < 0)
+    return fail(SLP_ERR_ARG, "classes, dim, batch must be positive and first_sample non-negative");
+  if (dt != SLP_F32 && dt != SLP_BF16) return fail(SLP_ERR_ARG, "unknown dtype %d", dt);
+  HIP_TRY(launch_make_inputs(seed, table, classes, y, first_sample, batch, dim, sigma, out, dt, (hipStream_t)stream));
+  return SLP_OK;
+}
+
+int slp_segment_create(const int* widths, int n_widths, int act, int loss, const slp_opts* opts, slp_segment** out) {
+  if (!widths || !opts || !out) return fail(SLP_ERR_ARG, "widths, opts and out must not be NULL");
+  *out = nullptr;
+  if (n_widths < 2) return fail(SLP_ERR_ARG, "a segment needs at least one layer (n_widths = %d)", n_widths);
+  if (n_widths > 65) return fail(SLP_ERR_ARG, "too many layers (%d)", n_widths - 1);
+  for (int i = 0; i < n_widths; ++i)
+    if (widths[i] <= 0 || widths[i] > (1 << 20)) return fail(SLP_ERR_ARG, "widths[%d] = %d is not in [1, 2^20]", i, widths[i]);
+  if (act != SLP_RELU_ALL && act != SLP_RELU_HIDDEN_IDENTITY_LAST) return fail(SLP_ERR_ARG, "unknown activation rule %d", act);
+  if (loss != SLP_MSE_SIL && loss != SLP_SOFTMAX_XENT) return fail(SLP_ERR_ARG, "unknown loss %d", loss);
+  if (opts->dtype != SLP_F32 && opts->dtype != SLP_BF16) return fail(SLP_ERR_ARG, "unknown dtype %d", opts->dtype);
+  if (opts->max_batch <= 0 || opts->max_batch > (1 << 24)) return fail(SLP_ERR_ARG, "max_batch = %d is not in [1, 2^24]", opts->max_batch);
+  if (!(opts->lr >= 0.0f) || !(opts->momentum >= 0.0f && opts->momentum < 1.0f))
+    return fail(SLP_ERR_ARG, "lr must be >= 0 and momentum in [0,1)");
+
+  slp_segment* s = new slp_segment();
+  s->L = n_widths - 1; s->act = act; s->loss = loss; s->dtype = opts->dtype; s->max_batch = opts->max_batch;
+  s->ldb = round_up(opts->max_batch, kLdAlign);
+  s->lr = opts->lr; s->mu = opts->momentum;
+  s->widths.assign(widths, widths + n_widths);
+  for (int w : s->widths) s->ldw.push_back(round_up(w, kLdAlign));
+  const size_t es = esize(s);
+
+  // every operand is addressed with 32-bit byte offsets below 2 GiB
+  for (int l = 0; l <= s->L; ++l) {
+    const size_t act_bytes = (size_t)std::max(s->ldb * (size_t)s->widths[l], (size_t)s->max_batch * s->ldw[l]) * es;
+    if (act_bytes >= 0x80000000ull) {
+      delete s;
+      return fail(SLP_ERR_SHAPE, "activation of layer %d (%zu bytes) exceeds the 2 GiB operand limit", l, act_bytes);
+    }
+  }
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  for (int l = 0; l < s->L; ++l) {
+    Layer ly{};
+    ly.K = widths[l]; ly.N = widths[l + 1];
+    ly.ldk = s->ldw[l]; ly.ldn = s->ldw[l + 1];
+    const size_t wbytes = (size_t)ly.N * ly.ldk * 4;
+    if (wbytes >= 0x80000000ull || (size_t)ly.K * ly.ldn * 4 >= 0x80000000ull) {
+      delete s;
+      return fail(SLP_ERR_SHAPE, "weight matrix of layer %d exceeds the 2 GiB operand limit", l);
+    }
+    ly.oW32 = take(wbytes); ly.ovW = take(wbytes); ly.odW = take(wbytes);
+    ly.ob = take((size_t)ly.N * 4); ly.ovb = take((size_t)ly.N * 4); ly.odb = take((size_t)ly.N * 4);
+    ly.oW16 = s->dtype == SLP_BF16 ? take((size_t)ly.N * ly.ldk * 2) : (size_t)-1;
+    ly.oWT = l > 0 ? take((size_t)ly.K * ly.ldn * es) : (size_t)-1;
+    s->layers.push_back(ly);
+  }
+  s->param_bytes = off;
+
+  off = 0;
+  s->oA.assign(s->L + 1, (size_t)-1); s->oAT = s->oA; s->odZ = s->oA; s->odZT = s->oA;
+  for (int l = 0; l <= s->L; ++l) {
+    s->oA[l] = take((size_t)s->max_batch * s->ldw[l] * es);
+    if (l < s->L) s->oAT[l] = take((size_t)s->widths[l] * s->ldb * es);
+    if (l >= 1) {
+      if (l >= 2 || l == s->L) s->odZ[l] = take((size_t)s->max_batch * s->ldw[l] * es);
+      s->odZT[l] = take((size_t)s->widths[l] * s->ldb * es);
+    }
+  }
+  s->n_partials = loss == SLP_MSE_SIL ? mse_partial_count(s->max_batch, s->widths[s->L]) : s->max_batch;
+  s->oPartials = take((size_t)s->n_partials * 4);
+  s->oLoss = take(4);
+  s->work_bytes = off;
+
+  s->bound = false; s->have_params = false; s->table = nullptr; s->classes = 0; s->last_batch = 0; s->prof = false;
+  s->partials = nullptr; s->loss_dev = nullptr;
+  *out = s;
+  return SLP_OK;
+}
+
+void slp_segment_destroy(slp_segment* seg) {
+  if (!seg) return;
+  for (auto& r : seg->prof_log) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  for (auto e : seg->ev_pool) hipEventDestroy(e);
+  delete seg;
+}
+
+size_t slp_segment_param_bytes(const slp_segment* seg) { return seg ? seg->param_bytes : 0; }
+size_t slp_segment_workspace_bytes(const slp_segment* seg) { return seg ? seg->work_bytes : 0; }
+
+int slp_segment_bind(slp_segment* seg, void* params, size_t params_bytes, void* workspace, size_t workspace_bytes,
+                     slp_stream stream) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  if (!params || !workspace) return fail(SLP_ERR_ARG, "params and workspace must not be NULL");
+  if (((uintptr_t)params | (uintptr_t)workspace) & (kAlign - 1)) return fail(SLP_ERR_ALLOC, "buffers must be 256-byte aligned");
+  if (params_bytes < seg->param_bytes) return fail(SLP_ERR_ALLOC, "params buffer has %zu bytes, %zu needed", params_bytes, seg->param_bytes);
+  if (workspace_bytes < seg->work_bytes) return fail(SLP_ERR_ALLOC, "workspace has %zu bytes, %zu needed", workspace_bytes, seg->work_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(hipMemsetAsync(params, 0, seg->param_bytes, st));
+  HIP_TRY(hipMemsetAsync(workspace, 0, seg->work_bytes, st));
+  char* p = (char*)params;
+  for (auto& ly : seg->layers) {
+    ly.W32 = (float*)(p + ly.oW32); ly.vW = (float*)(p + ly.ovW); ly.dW = (float*)(p + ly.odW);
+    ly.b = (float*)(p + ly.ob); ly.vb = (float*)(p + ly.ovb); ly.db = (float*)(p + ly.odb);
+    ly.W16 = ly.oW16 == (size_t)-1 ? nullptr : (void*)(p + ly.oW16);
+    ly.WT = ly.oWT == (size_t)-1 ? nullptr : (void*)(p + ly.oWT);
+    ly.Wop = ly.W16 ? ly.W16 : (void*)ly.W32;
+  }
+  char* w = (char*)workspace;
+  auto at = [&](size_t o) -> void* { return o == (size_t)-1 ? nullptr : (void*)(w + o); };
+  seg->A.clear(); seg->AT.clear(); seg->dZ.clear(); seg->dZT.clear();
+  for (int l = 0; l <= seg->L; ++l) {
+    seg->A.push_back(at(seg->oA[l])); seg->AT.push_back(at(seg->oAT[l]));
+    seg->dZ.push_back(at(seg->odZ[l])); seg->dZT.push_back(at(seg->odZT[l]));
+  }
+  seg->partials = (float*)at(seg->oPartials);
+  seg->loss_dev = (float*)at(seg->oLoss);
+  seg->bound = true;
+  seg->have_params = false;
+  return SLP_OK;
+}
+
+int slp_segment_init(slp_segment* seg, uint64_t seed, slp_stream stream) {
+  int rc = check_seg(seg, true, false);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  for (int l = 0; l < seg->L; ++l) {
+    Layer& ly = seg->layers[l];
+    HIP_TRY(launch_init_weights(seed, l, ly.W32, ly.N, ly.K, ly.ldk, ly.b, st));
+    HIP_TRY(hipMemsetAsync(ly.vW, 0, (size_t)ly.N * ly.ldk * 4, st));
+    HIP_TRY(hipMemsetAsync(ly.vb, 0, (size_t)ly.N * 4, st));
+    rc = refresh_copies(seg, l, st);
+    if (rc) return rc;
+  }
+  seg->have_params = true;
+  return SLP_OK;
+}
+
+int slp_segment_set_params(slp_segment* seg, int layer, const float* W, const float* b, int on_device, slp_stream stream) {
+  int rc = exchange(seg, layer, const_cast<float*>(W), const_cast<float*>(b), 0, true, on_device, (hipStream_t)stream);
+  if (rc == SLP_OK) seg->have_params = true;
+  return rc;
+}
+int slp_segment_get_params(slp_segment* seg, int layer, float* W, float* b, int on_device, slp_stream stream) {
+  return exchange(seg, layer, W, b, 0, false, on_device, (hipStream_t)stream);
+}
+int slp_segment_get_grads(slp_segment* seg, int layer, float* dW, float* db, int on_device, slp_stream stream) {
+  return exchange(seg, layer, dW, db, 1, false, on_device, (hipStream_t)stream);
+}
+int slp_segment_get_momentum(slp_segment* seg, int layer, float* vW, float* vb, int on_device, slp_stream stream) {
+  return exchange(seg, layer, vW, vb, 2, false, on_device, (hipStream_t)stream);
+}
+
+int slp_segment_get_activation(slp_segment* seg, int layer, int kind, int batch, void* out, slp_stream stream) {
+  int rc = check_seg(seg, true, false);
+  if (rc) return rc;
+  if (!out) return fail(SLP_ERR_ARG, "out is NULL");
+  if (layer < 0 || layer > seg->L || (kind != 0 && kind != 1)) return fail(SLP_ERR_ARG, "layer %d / kind %d out of range", layer, kind);
+  if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
+  hipStream_t st = (hipStream_t)stream;
+  const int w = seg->widths[layer];
+  if (kind == 0) {
+    HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[layer], seg->ldw[layer], batch, w, out, w, nullptr, 0, 0, st));
+  } else {
+    if (layer < 1) return fail(SLP_ERR_ARG, "no gradient is formed for the segment input");
+    if (seg->dZ[layer]) {
+      HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZ[layer], seg->ldw[layer], batch, w, out, w, nullptr, 0, 0, st));
+    } else {   // only the transposed copy exists: transpose it back
+      HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZT[layer], seg->ldb, w, batch, nullptr, 0, out, w, 0, st));
+    }
+  }
+  return SLP_OK;
+}
+
+int slp_segment_set_lr(slp_segment* seg, float lr, float momentum) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  if (!(lr >= 0.0f) || !(momentum >= 0.0f && momentum < 1.0f)) return fail(SLP_ERR_ARG, "lr must be >= 0 and momentum in [0,1)");
+  seg->lr = lr; seg->mu = momentum;
+  return SLP_OK;
+}
+
+int slp_segment_set_labels(slp_segment* seg, const float* table, int classes, int dim) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  if (seg->loss != SLP_MSE_SIL) return fail(SLP_ERR_STATE, "only a segment with the label-regression loss takes a label table");
+  if (!table || classes <= 0) return fail(SLP_ERR_ARG, "table must not be NULL and classes positive");
+  if (dim != seg->widths[seg->L]) return fail(SLP_ERR_SHAPE, "label dim %d != last width %d", dim, seg->widths[seg->L]);
+  seg->table = table; seg->classes = classes;
+  return SLP_OK;
+}
+
+int slp_segment_forward(slp_segment* seg, const void* X, int batch, void* out, slp_stream stream) {
+  int rc = check_seg(seg, true, true);
+  if (rc) return rc;
+  if (!X || !out) return fail(SLP_ERR_ARG, "X and out must not be NULL");
+  if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
+  hipStream_t st = (hipStream_t)stream;
+  rc = ingest(seg, X, batch, false, st);
+  if (rc) return rc;
+  rc = forward_layers(seg, batch, false, st);
+  if (rc) return rc;
+  const int w = seg->widths[seg->L];
+  HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[seg->L], seg->ldw[seg->L], batch, w, out, w, nullptr, 0, 0, st));
+  seg->last_batch = batch;
+  return SLP_OK;
+}
+
+int slp_segment_step(slp_segment* seg, const void* X, const int32_t* targets, int batch, float* loss_out, slp_stream stream) {
+  int rc = check_seg(seg, true, true);
+  if (rc) return rc;
+  if (!X || !targets) return fail(SLP_ERR_ARG, "X and targets must not be NULL");
+  if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
+  if (seg->loss == SLP_MSE_SIL && !seg->table) return fail(SLP_ERR_STATE, "no label table bound: call slp_segment_set_labels first");
+  hipStream_t st = (hipStream_t)stream;
+  const int L = seg->L, D = seg->widths[L];
+
+  rc = ingest(seg, X, batch, true, st);
+  if (rc) return rc;
+  rc = forward_layers(seg, batch, true, st);
+  if (rc) return rc;
+
+  // loss and dZ_L (row-major for the data gradient, transposed for the weight gradient)
+  if (seg->loss == SLP_MSE_SIL) {
+    HIP_TRY(launch_mse_loss_grad(seg->dtype, seg->A[L], seg->ldw[L], targets, seg->table, seg->classes, batch, D,
+                                 relu_on(seg, L) ? 1 : 0, seg->dZ[L], seg->dZT[L], seg->ldb, seg->partials, st));
+    HIP_TRY(launch_reduce_loss(seg->partials, mse_partial_count(batch, D), 1.0 / ((double)batch * D), seg->loss_dev, loss_out, st));
+  } else {
+    HIP_TRY(launch_xent_loss_grad(seg->dtype, seg->A[L], seg->ldw[L], targets, batch, D, relu_on(seg, L) ? 1 : 0,
+                                  seg->dZ[L], seg->partials, st));
+    HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZ[L], seg->ldw[L], batch, D, nullptr, 0, seg->dZT[L], seg->ldb, 1, st));
+    HIP_TRY(launch_reduce_loss(seg->partials, batch, 1.0 / (double)batch, seg->loss_dev, loss_out, st));
+  }
+
+  // backward + update, last layer first; the data gradient of layer l reads W_l before it is updated
+  for (int l = L; l >= 1; --l) {
+    Layer& ly = seg->layers[l - 1];
+    if (l > 1) {
+      GemmArgs g{};
+      g.A = seg->dZ[l]; g.lda = seg->ldw[l];
+      g.B = ly.WT;      g.ldb = ly.ldn;
+      g.M = batch; g.N = ly.K; g.K = ly.N;
+      g.C = seg->dZ[l - 1]; g.ldc = seg->ldw[l - 1];
+      g.CT = seg->dZT[l - 1]; g.ldct = seg->ldb;
+      g.maskT = seg->AT[l - 1]; g.ldmask = seg->ldb;
+      rc = run_gemm(seg, EPI_DGRAD, g, st);
+      if (rc) return rc;
+    }
+    {
+      GemmArgs g{};
+      g.A = seg->dZT[l];    g.lda = seg->ldb;
+      g.B = seg->AT[l - 1]; g.ldb = seg->ldb;
+      g.M = ly.N; g.N = ly.K; g.K = batch;
+      g.Cf = ly.dW; g.ldc = ly.ldk;
+      rc = run_gemm(seg, EPI_WGRAD, g, st);
+      if (rc) return rc;
+    }
+    HIP_TRY(launch_bias_grad(seg->dtype, seg->dZT[l], seg->ldb, ly.N, batch, ly.db, st));
+    HIP_TRY(launch_sgd_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->lr, seg->mu, 0, st));
+    HIP_TRY(launch_bias_update(ly.b, ly.vb, ly.db, ly.N, seg->lr, seg->mu, st));
+  }
+  seg->last_batch = batch;
+  return SLP_OK;
+}
+
+int slp_segment_profile_enable(slp_segment* seg, int on) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  seg->prof = on != 0;
+  // on > 1: create that many event pairs now, so that none is created between timed launches
+  for (int i = (int)seg->ev_pool.size(); on > 1 && i < 2 * on; ++i) {
+    hipEvent_t e = nullptr;
+    HIP_TRY(hipEventCreate(&e));
+    seg->ev_pool.push_back(e);
+  }
+  return SLP_OK;
+}
+
+int slp_segment_profile_read(slp_segment* seg, double* gemm_ms, int64_t* gemm_launches, double* gemm_flops) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  double ms = 0.0, fl = 0.0;
+  int64_t n = 0;
+  for (auto& r : seg->prof_log) {
+    HIP_TRY(hipEventSynchronize(r.b));
+    float t = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&t, r.a, r.b));
+    ms += t; fl += r.flops; ++n;
+    seg->ev_pool.push_back(r.a);
+    seg->ev_pool.push_back(r.b);
+  }
+  seg->prof_log.clear();
+  if (gemm_ms) *gemm_ms = ms;
+  if (gemm_launches) *gemm_launches = n;
+  if (gemm_flops) *gemm_flops = fl;
+  return SLP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,283 @@
+// Memory-bound kernels of the segment step: input ingest / transposes, the two
+// loss kernels (paper Sec. 2: regression on the synthetic label of the sample's
+// class for a non-final segment, classification for the final one), bias
+// gradients and the SGD-with-momentum update (Sec. 3).  All are written for
+// coalesced traffic (a wavefront touches consecutive addresses on both the read
+// and the write side; transposes go through LDS) and reduce with wavefront
+// shuffles in a fixed order, so results are bit-reproducible from run to run.
+#include "slp_kernels.h"
+
+namespace slp {
+namespace {
+
+typedef __bf16 bf16;
+
+template <typename T> __device__ __forceinline__ float to_f32(T v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v) { return (T)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+// ---------------------------------------------------------------------------------
+// copy + transpose through a 64x64 LDS tile
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void copy_transpose_kernel(const T* __restrict__ in, int ldin, int R, int C,
+                                                             T* __restrict__ out, int ldo, T* __restrict__ outT,
+                                                             int ldt, int pad_t) {
+  __shared__ T tile[64][65];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int rr = ty; rr < 64; rr += 4) {
+    const int r = r0 + rr, c = c0 + tx;
+    T v = from_f32<T>(0.0f);
+    if (r < R && c < C) {
+      v = in[(size_t)r * ldin + c];
+      if (out) out[(size_t)r * ldo + c] = v;
+    }
+    tile[rr][tx] = v;
+  }
+  if (!outT) return;
+  __syncthreads();
+  const int R8 = pad_t ? ((R + 7) & ~7) : R;
+  for (int cc = ty; cc < 64; cc += 4) {
+    const int c = c0 + cc, r = r0 + tx;
+    if (c < C && r < R8) outT[(size_t)c * ldt + r] = tile[tx][cc];
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// mean squared error against the synthetic label of each row's class
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void mse_loss_grad_kernel(const T* __restrict__ AL, int ld, const int32_t* __restrict__ y,
+                                                            const float* __restrict__ table, int classes, int B, int D,
+                                                            int relu_last,
+                                                            float scale, T* __restrict__ dZ, T* __restrict__ dZT, int ldt,
+                                                            float* __restrict__ partials) {
+  __shared__ T tile[64][65];
+  __shared__ float red[4];
+  const int b0 = blockIdx.y * 64, d0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  float lsum = 0.0f;
+  for (int rr = ty; rr < 64; rr += 4) {
+    const int m = b0 + rr, i = d0 + tx;
+    T gv = from_f32<T>(0.0f);
+    if (m < B && i < D) {
+      const float a = to_f32(AL[(size_t)m * ld + i]);
+      const int cls = min(max(y[m], 0), classes - 1);   // ids are the caller's; never index outside the table
+      const float d = a - table[(size_t)cls * D + i];
+      lsum += d * d;
+      const float g = (relu_last && !(a > 0.0f)) ? 0.0f : scale * d;
+      gv = from_f32<T>(g);
+      if (dZ) dZ[(size_t)m * ld + i] = gv;
+    }
+    tile[rr][tx] = gv;
+  }
+  lsum = wave_sum(lsum);
+  if (tx == 0) red[ty] = lsum;
+  __syncthreads();
+  if (threadIdx.x == 0) partials[blockIdx.y * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+  const int B8 = (B + 7) & ~7;
+  for (int dd = ty; dd < 64; dd += 4) {
+    const int i = d0 + dd, m = b0 + tx;
+    if (i < D && m < B8) dZT[(size_t)i * ldt + m] = tile[tx][dd];
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// softmax cross-entropy, one wavefront per row
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void xent_loss_grad_kernel(const T* __restrict__ ZL, int ld, const int32_t* __restrict__ y,
+                                                             int B, int C, int relu_last, float inv_b,
+                                                             T* __restrict__ dZ, float* __restrict__ row_loss) {
+  const int lane = threadIdx.x & 63;
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= B) return;
+  const T* z = ZL + (size_t)m * ld;
+  float mx = -INFINITY;
+  for (int c = lane; c < C; c += 64) mx = fmaxf(mx, to_f32(z[c]));
+  mx = wave_max(mx);
+  float sum = 0.0f;
+  for (int c = lane; c < C; c += 64) sum += expf(to_f32(z[c]) - mx);
+  sum = wave_sum(sum);
+  const float lse = mx + logf(sum);
+  const int cls = min(max(y[m], 0), C - 1);
+  if (lane == 0) row_loss[m] = lse - to_f32(z[cls]);
+  T* g = dZ + (size_t)m * ld;
+  for (int c = lane; c < C; c += 64) {
+    const float zc = to_f32(z[c]);
+    const float p = expf(zc - lse);
+    const float d = (p - (c == cls ? 1.0f : 0.0f)) * inv_b;
+    g[c] = from_f32<T>((relu_last && !(zc > 0.0f)) ? 0.0f : d);
+  }
+}
+
+// out = scale * sum(partials), summed in double in a fixed order by one block
+__global__ __launch_bounds__(256) void reduce_loss_kernel(const float* __restrict__ partials, int n, double scale,
+                                                          float* out0, float* out1) {
+  __shared__ double red[256];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) acc += (double)partials[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const float v = (float)(red[0] * scale);
+    out0[0] = v;
+    if (out1) out1[0] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// bias gradient: row sums of dZ^T, one wavefront per output feature
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dZT, int ldt, int N, int B,
+                                                        float* __restrict__ db) {
+  constexpr int V = 16 / sizeof(T);
+  typedef T vec_t __attribute__((ext_vector_type(V)));
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  const T* row = dZT + (size_t)n * ldt;
+  const int Bv = (B + V - 1) / V;      // pads up to the chunk boundary are zero
+  float acc = 0.0f;
+  for (int c = lane; c < Bv; c += 64) {
+    const vec_t v = *(const vec_t*)(row + (size_t)c * V);
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc += to_f32((T)v[e]);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) db[n] = acc;
+}
+
+// ---------------------------------------------------------------------------------
+// SGD with momentum on one weight matrix + derived copies
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32, float* __restrict__ vW,
+                                                         const float* __restrict__ dW, int N, int K, int ldk,
+                                                         bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
+                                                         float mu, int refresh_only) {
+  __shared__ T tile[64][65];
+  const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int rr = ty; rr < 64; rr += 4) {
+    const int n = n0 + rr, k = k0 + tx;
+    T wv = from_f32<T>(0.0f);
+    if (n < N && k < K) {
+      const size_t idx = (size_t)n * ldk + k;
+      float w = W32[idx];
+      if (!refresh_only) {
+        float v = dW[idx];
+        if (mu != 0.0f) {
+          v = mu * vW[idx] + v;
+          vW[idx] = v;
+        }
+        w = w - lr * v;
+        W32[idx] = w;
+      }
+      wv = from_f32<T>(w);
+      if (W16) W16[idx] = (bf16)w;
+    }
+    tile[rr][tx] = wv;
+  }
+  if (!WT) return;
+  __syncthreads();
+  for (int kk = ty; kk < 64; kk += 4) {
+    const int k = k0 + kk, n = n0 + tx;
+    if (k < K && n < N) WT[(size_t)k * ldn + n] = tile[tx][kk];
+  }
+}
+
+__global__ void bias_update_kernel(float* __restrict__ b, float* __restrict__ vb, const float* __restrict__ db, int N,
+                                   float lr, float mu) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  float v = db[n];
+  if (mu != 0.0f) {
+    v = mu * vb[n] + v;
+    vb[n] = v;
+  }
+  b[n] -= lr * v;
+}
+
+}  // namespace
+
+hipError_t launch_copy_transpose(int dtype, const void* in, int ldin, int R, int C, void* out, int ldo, void* outT,
+                                 int ldt, int pad_t, hipStream_t s) {
+  dim3 grid((C + 63) / 64, (R + 63) / 64);
+  if (dtype == 1)
+    copy_transpose_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)in, ldin, R, C, (bf16*)out, ldo, (bf16*)outT, ldt, pad_t);
+  else
+    copy_transpose_kernel<float><<<grid, 256, 0, s>>>((const float*)in, ldin, R, C, (float*)out, ldo, (float*)outT, ldt, pad_t);
+  return hipGetLastError();
+}
+
+int mse_partial_count(int B, int D) { return ((D + 63) / 64) * ((B + 63) / 64); }
+
+hipError_t launch_mse_loss_grad(int dtype, const void* AL, int ld, const int32_t* y, const float* table, int classes,
+                                int B, int D, int relu_last, void* dZ, void* dZT, int ldt, float* partials, hipStream_t s) {
+  dim3 grid((D + 63) / 64, (B + 63) / 64);
+  const float scale = (float)(2.0 / ((double)B * (double)D));
+  if (dtype == 1)
+    mse_loss_grad_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)AL, ld, y, table, classes, B, D, relu_last, scale, (bf16*)dZ,
+                                                    (bf16*)dZT, ldt, partials);
+  else
+    mse_loss_grad_kernel<float><<<grid, 256, 0, s>>>((const float*)AL, ld, y, table, classes, B, D, relu_last, scale, (float*)dZ,
+                                                     (float*)dZT, ldt, partials);
+  return hipGetLastError();
+}
+
+hipError_t launch_xent_loss_grad(int dtype, const void* ZL, int ld, const int32_t* y, int B, int C, int relu_last,
+                                 void* dZ, float* partials, hipStream_t s) {
+  const int grid = (B + 3) / 4;
+  const float inv_b = (float)(1.0 / (double)B);
+  if (dtype == 1)
+    xent_loss_grad_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)ZL, ld, y, B, C, relu_last, inv_b, (bf16*)dZ, partials);
+  else
+    xent_loss_grad_kernel<float><<<grid, 256, 0, s>>>((const float*)ZL, ld, y, B, C, relu_last, inv_b, (float*)dZ, partials);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_loss(const float* partials, int n, double scale, float* out0, float* out1, hipStream_t s) {
+  reduce_loss_kernel<<<1, 256, 0, s>>>(partials, n, scale, out0, out1);
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_grad(int dtype, const void* dZT, int ldt, int N, int B, float* db, hipStream_t s) {
+  const int grid = (N + 3) / 4;
+  if (dtype == 1) bias_grad_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)dZT, ldt, N, B, db);
+  else bias_grad_kernel<float><<<grid, 256, 0, s>>>((const float*)dZT, ldt, N, B, db);
+  return hipGetLastError();
+}
+
+hipError_t launch_sgd_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16,
+                             void* WT, int ldn, float lr, float mu, int refresh_only, hipStream_t s) {
+  dim3 grid((K + 63) / 64, (N + 63) / 64);
+  if (dtype == 1)
+    sgd_update_kernel<bf16><<<grid, 256, 0, s>>>(W32, vW, dW, N, K, ldk, (bf16*)W16, (bf16*)WT, ldn, lr, mu, refresh_only);
+  else
+    sgd_update_kernel<float><<<grid, 256, 0, s>>>(W32, vW, dW, N, K, ldk, nullptr, (float*)WT, ldn, lr, mu, refresh_only);
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_update(float* b, float* vb, const float* db, int N, float lr, float mu, hipStream_t s) {
+  bias_update_kernel<<<(N + 255) / 256, 256, 0, s>>>(b, vb, db, N, lr, mu);
+  return hipGetLastError();
+}
+
+}  // namespace slp

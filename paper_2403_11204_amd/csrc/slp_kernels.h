@@ -1,0 +1,79 @@
+// Internal launch interface between the C ABI (api.cpp) and the HIP kernels.
+// Not part of the public boundary; see include/slp.h for that.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace slp {
+
+// Leading dimensions of every internal buffer are multiples of this many elements,
+// so that each row starts on a 16-byte boundary for both element types and a
+// 16-byte chunk never straddles two rows.  Pad elements are zero.
+constexpr int kLdAlign = 8;
+inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
+
+enum Epilogue { EPI_FWD = 0, EPI_DGRAD = 1, EPI_WGRAD = 2 };
+
+// C[m][n] = sum_k A[m][k] * B[n][k]  ("NT": both operands contraction-contiguous).
+struct GemmArgs {
+  const void* A;   // [M][lda]
+  const void* B;   // [N][ldb]
+  int lda, ldb;
+  int M, N, K;     // logical sizes; pads up to the next chunk must be zero in A and B
+  // EPI_FWD  : v = acc + bias[n], optional ReLU; C (row-major) and/or CT (transposed) in T
+  // EPI_DGRAD: v = acc * [maskT[n][m] > 0];      C and/or CT in T
+  // EPI_WGRAD: Cf[m][n] = acc (float32)
+  void* C;         // [M][ldc] or null
+  void* CT;        // [N][ldct] or null; columns m in [M, round_up(M,8)) are written as zero
+  int ldc, ldct;
+  const float* bias;
+  int relu;
+  const void* maskT;  // [N][ldmask], element type T
+  int ldmask;
+  float* Cf;       // [M][ldc] float32
+};
+
+// dtype: 0 = float32 operands, 1 = bf16 operands (float32 accumulation in both).
+hipError_t launch_gemm(int dtype, int epi, const GemmArgs& g, hipStream_t s);
+// Name of the tile configuration launch_gemm would pick (for logs and profiles).
+const char* gemm_config_name(int dtype, int M, int N, int K);
+
+// in[R][ldin] -> out[R][ldo] (optional) and outT[C][ldt] (optional; with pad_t the
+// columns r in [R, round_up(R,8)) of outT are zero-filled).  Element type by dtype.
+hipError_t launch_copy_transpose(int dtype, const void* in, int ldin, int R, int C, void* out, int ldo, void* outT,
+                                 int ldt, int pad_t, hipStream_t s);
+
+// Mean-squared-error loss against table[y[m]] and its gradient w.r.t. the
+// pre-activation (ReLU mask applied when relu_last).  Writes dZ (row-major, optional),
+// dZT (transposed, zero-filled pads) and one partial sum per block.
+hipError_t launch_mse_loss_grad(int dtype, const void* AL, int ld, const int32_t* y, const float* table, int classes,
+                                int B, int D, int relu_last, void* dZ, void* dZT, int ldt, float* partials, hipStream_t s);
+int mse_partial_count(int B, int D);
+
+// Softmax cross-entropy per row: dZ[m][c] = (softmax - onehot)/B (zeroed where the
+// last layer's ReLU is inactive when relu_last), per-row loss to partials[m].
+hipError_t launch_xent_loss_grad(int dtype, const void* ZL, int ld, const int32_t* y, int B, int C, int relu_last,
+                                 void* dZ, float* partials, hipStream_t s);
+
+// out0[0] (and out1[0] if not null) = scale * sum(partials[0..n)), fixed summation order.
+hipError_t launch_reduce_loss(const float* partials, int n, double scale, float* out0, float* out1, hipStream_t s);
+
+// db[n] = sum_{m < B} dZT[n][m]
+hipError_t launch_bias_grad(int dtype, const void* dZT, int ldt, int N, int B, float* db, hipStream_t s);
+
+// SGD with momentum on one weight matrix: v = mu v + g; w -= lr v; then the derived
+// copies: W16 (bf16 [N][ldk], bf16 mode only) and WT ([K][ldn], element type T, optional).
+// refresh_only: skip the arithmetic and only rebuild the copies from W32.
+hipError_t launch_sgd_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16,
+                             void* WT, int ldn, float lr, float mu, int refresh_only, hipStream_t s);
+hipError_t launch_bias_update(float* b, float* vb, const float* db, int N, float lr, float mu, hipStream_t s);
+
+// Counter-based generators (Philox4x32-10).
+hipError_t launch_make_labels(uint64_t seed, int classes, int dim, int dist, float kappa, void* out, int dt,
+                              hipStream_t s);
+hipError_t launch_make_inputs(uint64_t seed, const float* table, int classes, const int32_t* y, int64_t first_sample,
+                              int batch, int dim, float sigma, void* out, int dt, hipStream_t s);
+hipError_t launch_init_weights(uint64_t seed, int layer, float* W32, int N, int K, int ldk, float* b, hipStream_t s);
+
+}  // namespace slp

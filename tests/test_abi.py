@@ -1,0 +1,97 @@
+"""The C-ABI library loads, exports every symbol include/slp.h declares, and turns
+bad arguments into error codes on the host before touching a device.  CPU only."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2403_11204_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "slp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slp_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared()
+    assert len(names) >= 18
+    L = api.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(api.EXPORTS) == names
+
+
+def _create(widths, act=api.RELU_ALL, loss=api.MSE_SIL, dtype=api.F32, max_batch=8, lr=0.01, mom=0.9):
+    L = api.lib()
+    arr = (ctypes.c_int * len(widths))(*widths)
+    opts = api._Opts(dtype, max_batch, lr, mom)
+    h = ctypes.c_void_p()
+    rc = L.slp_segment_create(arr, len(widths), act, loss, ctypes.byref(opts), ctypes.byref(h))
+    return rc, h
+
+
+def test_create_rejects_bad_arguments():
+    L = api.lib()
+    assert _create([4])[0] == -1                       # no layer
+    assert _create([4, 0, 3])[0] == -1                 # width <= 0
+    assert _create([4, 3], act=7)[0] == -1
+    assert _create([4, 3], loss=-2)[0] == -1
+    assert _create([4, 3], dtype=5)[0] == -1
+    assert _create([4, 3], max_batch=0)[0] == -1
+    assert _create([4, 3], mom=1.5)[0] == -1
+    assert b"momentum" in L.slp_last_error()
+    opts = api._Opts(0, 8, 0.01, 0.9)
+    h = ctypes.c_void_p()
+    assert L.slp_segment_create(None, 2, 0, 0, ctypes.byref(opts), ctypes.byref(h)) == -1
+    # 2^20 x 2^20 weights cannot be addressed
+    assert _create([1 << 20, 1 << 20])[0] == -2
+
+
+def test_sizes_and_state_errors_without_device():
+    L = api.lib()
+    rc, h = _create([784, 80, 60], max_batch=1410)
+    assert rc == 0 and h.value
+    pb, wb = L.slp_segment_param_bytes(h), L.slp_segment_workspace_bytes(h)
+    # at least master + momentum + gradient for every parameter of the paper's left partition (Sec. 3)
+    assert pb >= 3 * 4 * 67660 and pb % 256 == 0
+    assert wb >= 4 * 1410 * (784 + 80 + 60) and wb % 256 == 0
+    dummy = ctypes.c_void_p(0x1000)
+    # nothing bound yet
+    assert L.slp_segment_step(h, dummy, dummy, 8, None, None) == -5
+    assert L.slp_segment_forward(h, dummy, 8, dummy, None) == -5
+    assert L.slp_segment_init(h, 1, None) == -5
+    assert L.slp_segment_get_params(h, 0, dummy, dummy, 1, None) == -5
+    assert b"bind" in L.slp_last_error()
+    # bind validation happens before any device call
+    assert L.slp_segment_bind(h, None, pb, dummy, wb, None) == -1
+    assert L.slp_segment_bind(h, ctypes.c_void_p(0x1001), pb, ctypes.c_void_p(0x1000), wb, None) == -3
+    assert L.slp_segment_bind(h, ctypes.c_void_p(0x1000), pb - 1, ctypes.c_void_p(0x1000), wb, None) == -3
+    # labels: wrong width, and a classification segment takes none
+    assert L.slp_segment_set_labels(h, dummy, 47, 61) == -2
+    assert L.slp_segment_set_labels(h, dummy, 47, 60) == 0
+    assert L.slp_segment_set_lr(h, -1.0, 0.9) == -1
+    assert L.slp_segment_set_lr(h, 0.1, 0.0) == 0
+    L.slp_segment_destroy(h)
+    rc, h2 = _create([60, 60, 60, 47], act=api.RELU_HIDDEN_IDENTITY_LAST, loss=api.SOFTMAX_XENT)
+    assert rc == 0
+    assert L.slp_segment_set_labels(h2, dummy, 47, 47) == -5
+    L.slp_segment_destroy(h2)
+    assert L.slp_segment_step(None, dummy, dummy, 8, None, None) == -1
+    assert L.slp_segment_param_bytes(None) == 0
+
+
+def test_free_functions_reject_bad_arguments():
+    L = api.lib()
+    dummy = ctypes.c_void_p(0x1000)
+    assert L.slp_make_synthetic_labels(1, 0, 8, 0, 1.0, dummy, 0, None) == -1
+    assert L.slp_make_synthetic_labels(1, 4, 8, 9, 1.0, dummy, 0, None) == -1
+    assert L.slp_make_synthetic_labels(1, 4, 8, 0, 1.0, None, 0, None) == -1
+    assert L.slp_make_synthetic_labels(1, 4, 8, 0, 1.0, dummy, 3, None) == -1
+    assert L.slp_make_segment_inputs(1, None, 4, dummy, 0, 2, 8, 0.05, dummy, 0, None) == -1
+    assert L.slp_make_segment_inputs(1, dummy, 4, dummy, -1, 2, 8, 0.05, dummy, 0, None) == -1

@@ -1,0 +1,269 @@
+"""HIP path against the CPU oracle, element by element, through the C ABI.
+
+Tolerances (per tensor, max|gpu - ref| / max|ref|):
+  float32 path  1e-5   (float32 MFMA accumulation against float64)
+  bf16 path     2e-2   (bf16 storage, float32 accumulation)
+Labels, generated inputs, initial weights and gather indices are bit-exact."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rng as orng
+from oracle import segment as osg
+from paper_2403_11204_amd import api, datagen
+
+pytestmark = pytest.mark.gpu
+
+TOL = {api.F32: 1e-5, api.BF16: 2e-2}
+DEV = "cuda"
+
+
+def rel_err(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    return float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+
+
+def to_np(t):
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+def as_input(X, dtype):
+    """Host float32 inputs -> (device tensor in the handle's dtype, the exact values it holds as float64)."""
+    t = torch.from_numpy(np.ascontiguousarray(X)).to(DEV)
+    t = t.to(torch.bfloat16) if dtype == api.BF16 else t
+    return t.contiguous(), to_np(t).astype(np.float64)
+
+
+# ---------------------------------------------------------------------------------
+# generators: bit-exact
+# ---------------------------------------------------------------------------------
+@pytest.mark.parametrize("dist", [api.UNIFORM01, api.UNIFORM_PM1, api.NORMAL, api.BINARY_PM1])
+@pytest.mark.parametrize("classes,dim,seed,kappa", [(47, 64, 7, 1.0), (47, 60, 11, 10.0), (47, 2048, 13, 1.0),
+                                                    (100, 8192, (21 << 32) | 5, 2.5), (3, 1, 0, 1.0)])
+def test_labels_bit_exact(dist, classes, dim, seed, kappa):
+    ref = orng.make_synthetic_labels(seed, classes, dim, dist, kappa)
+    got = api.make_synthetic_labels(seed, classes, dim, dist, kappa, api.F32)
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    got16 = api.make_synthetic_labels(seed, classes, dim, dist, kappa, api.BF16)
+    ref16 = orng.round_to_bf16(ref)
+    assert np.array_equal(to_np(got16).view(np.uint32), ref16.view(np.uint32))
+
+
+def test_labels_bit_exact_largest_table():
+    # 1000 x 16384 U(-1,1) (comparison config) and N(0,1): every one of the 16.4 M entries
+    for dist, seed in ((api.UNIFORM_PM1, 31), (api.NORMAL, 23)):
+        got = api.make_synthetic_labels(seed, 1000, 16384, dist).cpu().numpy()
+        ref = orng.make_synthetic_labels(seed, 1000, 16384, dist)
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+def test_segment_inputs_bit_exact(dtype):
+    table = api.make_synthetic_labels(7, 47, 64, api.UNIFORM_PM1)
+    y = datagen.balanced_classes(300, 47, first=5)
+    first = (1 << 32) - 100          # crosses the 32-bit boundary of the sample counter
+    got = api.make_segment_inputs(5, table, torch.from_numpy(y).to(DEV), first, 0.05, dtype)
+    ref = orng.make_segment_inputs(5, table.cpu().numpy(), y, first, 0.05)
+    if dtype == api.BF16:
+        ref = orng.round_to_bf16(ref)
+    assert np.array_equal(to_np(got).view(np.uint32), ref.view(np.uint32))
+
+
+def test_init_weights_bit_exact():
+    widths = [37, 70, 129, 47]
+    seg = api.Segment(widths, api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, max_batch=8)
+    seg.init(3)
+    for l in range(3):
+        W, b = seg.get_params(l)
+        rW, rb = orng.init_weights(3, l, widths[l + 1], widths[l])
+        assert np.array_equal(W.cpu().numpy().view(np.uint32), rW.view(np.uint32))
+        assert np.array_equal(b.cpu().numpy().view(np.uint32), rb.view(np.uint32))
+
+
+# ---------------------------------------------------------------------------------
+# one training step and short runs
+# ---------------------------------------------------------------------------------
+def make_pair(widths, act, loss, dtype, max_batch, lr, mom, wseed):
+    g = api.Segment(widths, act, loss, max_batch=max_batch, dtype=dtype, lr=lr, momentum=mom)
+    o = osg.Segment(widths, act, loss, lr=lr, momentum=mom, mode="bf16" if dtype == api.BF16 else "fp32")
+    for l, (W, b) in enumerate(datagen.uniform_weights(widths, wseed)):
+        g.set_params(l, torch.from_numpy(W), torch.from_numpy(b))
+        o.set_params(l, W, b)
+    return g, o
+
+
+def check_step(g, o, X, y, table_np, dtype, steps=1, check_internals=True):
+    tol = TOL[dtype]
+    B = X.shape[0]
+    Xd, Xv = as_input(X, dtype)
+    yd = torch.from_numpy(y).to(DEV)
+    if table_np is not None:
+        g.set_labels(torch.from_numpy(table_np).to(DEV))
+    W_before = [o.W[l].copy() for l in range(o.L)]
+    for s in range(steps):
+        loss_g = float(g.step(Xd, yd).item())
+        out = o.step(Xv, y, table_np)
+        assert abs(loss_g - out["loss"]) <= tol * abs(out["loss"]), (s, loss_g, out["loss"])
+    if check_internals:      # state of the last step
+        for l in range(1, o.L + 1):
+            assert rel_err(to_np(g.get_activation(l, B)), out["A"][l]) <= tol, ("A", l)
+            # near a ReLU tie the two sides may legitimately disagree on the mask: leave those out
+            dz_ref = out["dZ"][l]
+            dz_got = to_np(g.get_activation(l, B, kind=1)).astype(np.float64)
+            relu_here = l < o.L or o.act == osg.RELU_ALL
+            if relu_here:
+                tie = np.abs(out["Z"][l]) < 1e-4 * np.max(np.abs(out["Z"][l]))
+                dz_got = np.where(tie, dz_ref, dz_got)
+            assert rel_err(dz_got, dz_ref) <= tol, ("dZ", l)
+        for l in range(o.L):
+            dW, db = g.get_grads(l)
+            assert rel_err(to_np(dW), out["dW"][l]) <= tol, ("dW", l)
+            assert rel_err(to_np(db), out["db"][l]) <= tol, ("db", l)
+    for l in range(o.L):
+        W, b = g.get_params(l)
+        assert rel_err(to_np(W), o.W[l]) <= tol, ("W", l)
+        assert rel_err(to_np(b), o.b[l]) <= tol, ("b", l)
+        # the update itself, not hidden behind the size of the weights
+        # (float32 storage of W puts a floor of a few ulp(|W|) under what can be seen of it)
+        d_got, d_ref = to_np(W).astype(np.float64) - W_before[l], o.W[l] - W_before[l]
+        floor = 4.0 * float(np.spacing(np.float32(np.max(np.abs(o.W[l])))))
+        assert np.max(np.abs(d_got - d_ref)) <= tol * np.max(np.abs(d_ref)) + floor, ("dWstep", l)
+        if o.mu != 0.0:
+            vW, vb = g.get_momentum(l)
+            assert rel_err(to_np(vW), o.vW[l]) <= tol, ("vW", l)
+            assert rel_err(to_np(vb), o.vb[l]) <= tol, ("vb", l)
+
+
+CASES = [
+    # name, widths, act, loss, B, dist, classes
+    ("tinyA", [784, 128, 64], api.RELU_ALL, api.MSE_SIL, 64, api.UNIFORM_PM1, 47),
+    ("tinyB", [64, 64, 47], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, 64, None, 47),
+    ("ragged", [37, 70, 129, 47], api.RELU_ALL, api.MSE_SIL, 100, api.NORMAL, 10),
+    ("raggedCE", [45, 131, 66, 10], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, 77, None, 10),
+    ("one_layer", [20, 12], api.RELU_HIDDEN_IDENTITY_LAST, api.MSE_SIL, 9, api.UNIFORM01, 5),
+    ("reluCE", [24, 40, 16], api.RELU_ALL, api.SOFTMAX_XENT, 33, None, 16),
+    ("paperA", [784, 1024, 1024, 512], api.RELU_ALL, api.MSE_SIL, 256, api.NORMAL, 47),
+    ("paperB", [512, 1024, 1024, 47], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, 256, None, 47),
+    ("paper_sec3_left", [784, 80, 60], api.RELU_ALL, api.MSE_SIL, 1410, api.UNIFORM01, 47),
+    ("paper_sec3_right", [60, 60, 60, 47], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, 1410, None, 47),
+]
+
+
+def case_data(widths, loss, B, dist, classes, seed):
+    X, y = datagen.class_mean_inputs(B, classes, dim=widths[0], seed=seed)
+    table = None
+    if loss == api.MSE_SIL:
+        kappa = 10.0 if dist == api.UNIFORM01 else 1.0
+        table = orng.make_synthetic_labels(seed + 10, classes, widths[-1], dist, kappa)
+    return X, y, table
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_one_step(case, dtype):
+    name, widths, act, loss, B, dist, classes = case
+    X, y, table = case_data(widths, loss, B, dist, classes, seed=1)
+    g, o = make_pair(widths, act, loss, dtype, max_batch=B, lr=0.01, mom=0.9, wseed=3)
+    check_step(g, o, X, y, table, dtype)
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+def test_plain_sgd_and_smaller_batches_on_one_handle(dtype):
+    # momentum 0 path; then a shorter, ragged batch on the same handle (stale pad columns must not leak)
+    widths = [48, 96, 40]
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, dtype, max_batch=200, lr=0.05, mom=0.0, wseed=5)
+    X, y, table = case_data(widths, api.MSE_SIL, 200, api.UNIFORM_PM1, 12, seed=2)
+    check_step(g, o, X, y, table, dtype)
+    check_step(g, o, X[:61], y[:61], table, dtype)
+    check_step(g, o, X[3:12], y[3:12], table, dtype)
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+def test_several_steps_with_momentum(dtype):
+    widths = [64, 96, 80, 32]
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, dtype, max_batch=128, lr=0.02, mom=0.9, wseed=6)
+    X, y, table = case_data(widths, api.MSE_SIL, 128, api.UNIFORM01, 20, seed=4)
+    check_step(g, o, X, y, table, dtype, steps=5, check_internals=(dtype == api.F32))
+
+
+def test_wide_bf16_config_one_step():
+    # the wide 3|3 split at its real shape: 784-4096-4096-2048 (+-1 labels) and 2048-4096-4096-47, batch 1024
+    X, y = datagen.class_mean_inputs(1024, 47, dim=784, seed=1)
+    table = orng.make_synthetic_labels(13, 47, 2048, api.BINARY_PM1)
+    g, o = make_pair([784, 4096, 4096, 2048], api.RELU_ALL, api.MSE_SIL, api.BF16, 1024, 0.01, 0.9, wseed=7)
+    check_step(g, o, X, y, table, api.BF16)
+    XB = orng.make_segment_inputs(5, table, y, 0, 0.05)
+    g, o = make_pair([2048, 4096, 4096, 47], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, api.BF16, 1024, 0.01, 0.9, wseed=8)
+    check_step(g, o, XB, y, None, api.BF16)
+
+
+def test_tiny_config_epoch_loss_curve():
+    # tiny config: 2048 blob images, batch 64, lr 0.01, one epoch, both segments, float32
+    X, y = datagen.blob_images(2048, 47, 28, seed=1)
+    table = orng.make_synthetic_labels(7, 47, 64, api.UNIFORM_PM1)
+    gA, oA = make_pair([784, 128, 64], api.RELU_ALL, api.MSE_SIL, api.F32, 64, 0.01, 0.0, wseed=3)
+    gB, oB = make_pair([64, 64, 47], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, api.F32, 64, 0.01, 0.0, wseed=4)
+    gA.set_labels(torch.from_numpy(table).to(DEV))
+    XB = orng.make_segment_inputs(5, table, y, 0, 0.05)
+    Xd, Xv = as_input(X, api.F32)
+    XBd, XBv = as_input(XB, api.F32)
+    yd = torch.from_numpy(y).to(DEV)
+    la, lb, ra, rb = [], [], [], []
+    for s in range(0, 2048, 64):
+        la.append(gA.step(Xd[s:s + 64], yd[s:s + 64]).item())
+        lb.append(gB.step(XBd[s:s + 64], yd[s:s + 64]).item())
+        ra.append(oA.step(Xv[s:s + 64], y[s:s + 64], table)["loss"])
+        rb.append(oB.step(XBv[s:s + 64], y[s:s + 64])["loss"])
+    assert np.max(np.abs(np.array(la) - ra) / np.array(ra)) <= 1e-5
+    assert np.max(np.abs(np.array(lb) - rb) / np.array(rb)) <= 1e-5
+    for l in range(2):
+        assert rel_err(to_np(gA.get_params(l)[0]), oA.W[l]) <= 1e-5
+        assert rel_err(to_np(gB.get_params(l)[0]), oB.W[l]) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+def test_forward_only_and_determinism(dtype):
+    widths = [100, 300, 77]
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, dtype, max_batch=500, lr=0.01, mom=0.9, wseed=9)
+    X, y, table = case_data(widths, api.MSE_SIL, 500, api.NORMAL, 7, seed=3)
+    Xd, Xv = as_input(X, dtype)
+    out1 = g.forward(Xd)
+    assert rel_err(to_np(out1), o.forward(Xv)) <= TOL[dtype]
+    out2 = g.forward(Xd)
+    assert torch.equal(out1, out2)
+    W0 = [g.get_params(l)[0].clone() for l in range(2)]
+    for l in range(2):                                   # forward changes no parameter
+        assert torch.equal(W0[l], g.get_params(l)[0])
+    # two identical handles stepping on the same data stay bit-identical (fixed summation order)
+    g2, _ = make_pair(widths, api.RELU_ALL, api.MSE_SIL, dtype, 500, 0.01, 0.9, wseed=9)
+    tb = torch.from_numpy(table).to(DEV)
+    g.set_labels(tb)
+    g2.set_labels(tb)
+    yd = torch.from_numpy(y).to(DEV)
+    for _ in range(3):
+        l1 = g.step(Xd, yd).clone()
+        l2 = g2.step(Xd, yd).clone()
+        assert torch.equal(l1, l2)
+    for l in range(2):
+        assert torch.equal(g.get_params(l)[0], g2.get_params(l)[0])
+
+
+def test_step_argument_errors():
+    g, _ = make_pair([16, 8], api.RELU_ALL, api.MSE_SIL, api.F32, 32, 0.01, 0.9, wseed=1)
+    X = torch.zeros((64, 16), device=DEV)
+    y = torch.zeros(64, dtype=torch.int32, device=DEV)
+    with pytest.raises(api.SlpError) as e:
+        g.step(X[:8], y[:8])                  # no labels bound
+    assert e.value.code == -5
+    g.set_labels(torch.zeros((3, 8), device=DEV))
+    with pytest.raises(api.SlpError) as e:
+        g.step(X, y)                          # batch above max_batch
+    assert e.value.code == -2
+    fresh = api.Segment([16, 8], api.RELU_ALL, api.MSE_SIL, max_batch=32)
+    fresh.set_labels(torch.zeros((3, 8), device=DEV))
+    with pytest.raises(api.SlpError) as e:
+        fresh.step(X[:8], y[:8])              # no parameters yet
+    assert e.value.code == -5
