@@ -28,7 +28,7 @@ COMMON = [
 ]
 UNITS = {
     "api.hip": [],
-    "rng.hip": ["-ffp-contract=off"],
+    "rng.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
     "elementwise.hip": [],
     "gemm.hip": [],
 }

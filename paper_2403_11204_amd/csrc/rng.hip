@@ -34,6 +34,11 @@ __device__ __forceinline__ Words philox4x32_10(uint32_t c0, uint32_t c1, uint32_
   return Words{c0, c1, c2, c3};
 }
 
+// IEEE square root: the plain builtin is lowered to the correctly rounded sequence
+// (this file is built with -fhip-fp32-correctly-rounded-divide-sqrt); the
+// "__fsqrt_rn" spelling maps to the 1-ulp native instruction and must not be used.
+__device__ __forceinline__ float correctly_rounded_sqrt(float x) { return __builtin_sqrtf(x); }
+
 __device__ __forceinline__ float unit_uniform(uint32_t r) {   // (r >> 8) * 2^-24, exact
   return __fmul_rn((float)(r >> 8), 0x1p-24f);
 }
@@ -80,7 +85,7 @@ __device__ __forceinline__ float cos_turn(uint32_t k) {
 
 __device__ __forceinline__ float standard_normal(uint32_t r0, uint32_t r1) {
   const float u1 = __fmul_rn((float)((r0 >> 8) + 1u), 0x1p-24f);
-  const float radius = __fsqrt_rn(__fmul_rn(-2.0f, ln_unit(u1)));
+  const float radius = correctly_rounded_sqrt(__fmul_rn(-2.0f, ln_unit(u1)));
   return __fmul_rn(radius, cos_turn(r1 >> 8));
 }
 
@@ -127,7 +132,7 @@ __global__ void inputs_kernel(uint32_t k0, uint32_t k1, const float* __restrict_
 }
 
 __global__ void init_kernel(uint32_t k0, uint32_t k1, uint32_t layer, float* W, int N, int K, int ldk, float* b) {
-  const float bound = __fdiv_rn(1.0f, __fsqrt_rn((float)K));
+  const float bound = __fdiv_rn(1.0f, correctly_rounded_sqrt((float)K));
   const size_t total = (size_t)N * (K + 1);
   for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
     const uint32_t o = (uint32_t)(e / (K + 1)), k = (uint32_t)(e % (K + 1));

@@ -108,16 +108,27 @@ def check_step(g, o, X, y, table_np, dtype, steps=1, check_internals=True):
         out = o.step(Xv, y, table_np)
         assert abs(loss_g - out["loss"]) <= tol * abs(out["loss"]), (s, loss_g, out["loss"])
     if check_internals:      # state of the last step
-        for l in range(1, o.L + 1):
-            assert rel_err(to_np(g.get_activation(l, B)), out["A"][l]) <= tol, ("A", l)
-            # near a ReLU tie the two sides may legitimately disagree on the mask: leave those out
+        # The ReLU mask is an integer decision taken from a floating-point value.  Where the
+        # oracle's pre-activation is a near-tie the two sides may legitimately decide
+        # differently; such an element is valid on both sides, but it changes the whole row of
+        # every dZ below it.  So: every disagreement must be a near-tie and they must be rare;
+        # rows that contain one are compared in the L2 sense only, all other rows element-wise.
+        flipped_rows = np.zeros(B, dtype=bool)
+        for l in range(o.L, 0, -1):
+            a_got = to_np(g.get_activation(l, B)).astype(np.float64)
+            assert rel_err(a_got, out["A"][l]) <= tol, ("A", l)
+            if l < o.L or o.act == osg.RELU_ALL:
+                mism = (a_got > 0) != (out["A"][l] > 0)
+                if mism.any():
+                    assert np.all(np.abs(out["Z"][l][mism]) <= 1e-3 * np.max(np.abs(out["Z"][l]))), ("mask", l)
+                    assert mism.mean() <= 1e-4, ("mask rate", l, mism.mean())
+                    flipped_rows |= mism.any(axis=1)
             dz_ref = out["dZ"][l]
             dz_got = to_np(g.get_activation(l, B, kind=1)).astype(np.float64)
-            relu_here = l < o.L or o.act == osg.RELU_ALL
-            if relu_here:
-                tie = np.abs(out["Z"][l]) < 1e-4 * np.max(np.abs(out["Z"][l]))
-                dz_got = np.where(tie, dz_ref, dz_got)
-            assert rel_err(dz_got, dz_ref) <= tol, ("dZ", l)
+            assert np.linalg.norm(dz_got - dz_ref) <= tol * np.linalg.norm(dz_ref), ("dZ L2", l)
+            keep = ~flipped_rows
+            assert keep.mean() >= 0.9
+            assert np.max(np.abs(dz_got[keep] - dz_ref[keep])) <= tol * np.max(np.abs(dz_ref)), ("dZ", l)
         for l in range(o.L):
             dW, db = g.get_grads(l)
             assert rel_err(to_np(dW), out["dW"][l]) <= tol, ("dW", l)
