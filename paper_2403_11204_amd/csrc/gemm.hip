@@ -13,21 +13,34 @@
 //
 // gfx950 mapping
 //   * 256 threads = 4 wavefronts in a 2x2 grid; a wavefront owns a (BM/2)x(BN/2)
-//     sub-tile as MIxNI MFMA 32x32 blocks, accumulators in registers (AGPRs).
+//     sub-tile as MIxNI MFMA 32x32 blocks, accumulators in AGPRs (256 of them for the
+//     256x256 tile: one wavefront per SIMD, 128x128 outputs per wavefront, which is the
+//     blocking with the fewest LDS bytes per MFMA).
 //   * bf16: v_mfma_f32_32x32x16_bf16, one per 16-byte chunk pair; float32:
 //     v_mfma_f32_32x32x2_f32, four per 16-byte chunk pair.  A k-tile is 128 bytes
 //     per row for both types (64 bf16 / 32 float), so loads, LDS layout and
 //     addressing are byte-identical for the two types.
-//   * global -> registers with buffer loads (out-of-range rows and k-tail chunks read
-//     as zero through the resource's range check), registers -> LDS, double buffered:
-//     tile k+1 is in flight while tile k is multiplied; one barrier per k-tile.
-//   * LDS rows are 128 bytes; the 16-byte chunk index is XOR-ed with (row & 7) so the
-//     8 lanes served together by a ds_read_b128 / ds_write_b128 hit 8 different bank
-//     groups.
+//   * global -> LDS directly (buffer_load_dwordx4 ... lds): no staging registers and
+//     no ds_write instructions (a burst of 16-byte LDS writes stalls the LDS pipe for
+//     ~13 cycles per wavefront instruction; measured, it was the largest stall).
+//     Out-of-range rows and k-tail chunks read as zero through the buffer resource's
+//     range check, so ragged M, N and K need no branches.
+//   * two LDS stages of (BM+BN) x 128 bytes; the loads of tile k+2 are issued as soon as
+//     the barrier after sub-step 2 of tile k has freed its stage; one barrier per k-tile.
+//   * every k-tile is 4 sub-steps of MIxNI MFMAs; the fragments of sub-step s+1 are read
+//     from LDS while sub-step s multiplies, and the source order "2 LDS reads, 2 loads,
+//     2 MFMAs" is pinned with scheduling fences, because the compiler's own schedule
+//     serialises LDS latency with the matrix pipe.
+//   * LDS rows are 128 bytes and the LDS has 64 banks x 4 bytes: a ds_read_b128 is served
+//     16 lanes at a time, i.e. 16 consecutive rows of one k-chunk.  Physical chunk =
+//     chunk ^ ((row >> 1) & 7) spreads those 16 rows over all 64 banks (measured 5.8 vs
+//     8.0 cycles per wavefront read for the naive (row & 7) swizzle).  The hardware writes
+//     lane l of an LDS-direct load at base + 16 l, so the swizzle is applied on the global
+//     side: each lane fetches the chunk that belongs at its physical position.
 //   * workgroup -> tile: consecutive workgroup ids go round-robin over the 8 XCDs, so
 //     ids are first regrouped per XCD (each XCD gets a contiguous range of tiles and
-//     its own L2 sees a compact set of operand rows), then walked in column-major
-//     groups of 8 tile-rows.
+//     its own 4 MB L2 sees a compact set of operand rows: measured L2 hit rate 79%), then
+//     walked in column-major groups of 8 tile-rows.
 #include "slp_kernels.h"
 
 namespace slp {
@@ -63,6 +76,7 @@ template <> struct Vec4<float> { typedef f32x4 type; };
 
 template <typename T, int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
+#if defined(__HIP_DEVICE_COMPILE__)   // LDS-direct builtins exist in the device pass only; the host pass needs just the launch stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int ES = sizeof(T);
   constexpr int CH = Chunk<T>::elems;        // elements per 16-byte chunk
@@ -91,45 +105,32 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
   const int half = lane >> 5, l32 = lane & 31;
 
   // ---- global load addressing --------------------------------------------------------
-  const int kc = t & 7, lrow = t >> 3;       // chunk column and first row handled by this thread
   const int Kr = (g.K + CH - 1) / CH * CH;   // chunk-granular contraction length
   const __amdgpu_buffer_rsrc_t rsrcA =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.A), 0, (int)((size_t)g.M * g.lda * ES), 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcB =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.B), 0, (int)((size_t)g.N * g.ldb * ES), 0x00020000);
+  // Direct-to-LDS loads: load i of wavefront w fills LDS rows [8w + 32i, 8w + 32i + 8) of the tile,
+  // lane l writing 16 bytes at (row 8w + 32i + l/8, physical chunk l%8) -- the hardware places lane l
+  // at base + 16*l.  The XOR swizzle is therefore applied on the global side: the lane fetches the
+  // logical chunk that belongs at its physical position.
+  const int prow = w * 8 + (lane >> 3);                   // + 32 i
+  const int pchunk = (lane & 7) ^ ((prow >> 1) & 7);      // logical k-chunk fetched by this lane
   uint32_t voffA[LA], voffB[LB];
 #pragma unroll
-  for (int i = 0; i < LA; ++i) voffA[i] = (uint32_t)(((size_t)(m0 + lrow + 32 * i) * g.lda + kc * CH) * ES);
+  for (int i = 0; i < LA; ++i) voffA[i] = (uint32_t)(((size_t)(m0 + prow + 32 * i) * g.lda + pchunk * CH) * ES);
 #pragma unroll
-  for (int i = 0; i < LB; ++i) voffB[i] = (uint32_t)(((size_t)(n0 + lrow + 32 * i) * g.ldb + kc * CH) * ES);
-  // rows past the end give offsets >= the resource size and read as zero
-  const uint32_t lds_wr = (uint32_t)(lrow * 128 + ((kc ^ (lrow & 7)) << 4));
-
-  u32x4 ga[LA], gb[LB];
-  auto load_global = [&](int kt) {
-    const bool in_k = kt * BK + kc * CH < Kr;
-    const uint32_t koff = (uint32_t)kt * 128u;
-#pragma unroll
-    for (int i = 0; i < LA; ++i)
-      ga[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, in_k ? voffA[i] + koff : kOutOfRange, 0, 0);
-#pragma unroll
-    for (int i = 0; i < LB; ++i)
-      gb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, in_k ? voffB[i] + koff : kOutOfRange, 0, 0);
-  };
-  auto store_lds = [&](int stage) {
-    unsigned char* base = smem + stage * STAGE + lds_wr;
-#pragma unroll
-    for (int i = 0; i < LA; ++i) *(u32x4*)(base + i * 32 * 128) = ga[i];
-#pragma unroll
-    for (int i = 0; i < LB; ++i) *(u32x4*)(base + A_BYTES + i * 32 * 128) = gb[i];
-  };
+  for (int i = 0; i < LB; ++i) voffB[i] = (uint32_t)(((size_t)(n0 + prow + 32 * i) * g.ldb + pchunk * CH) * ES);
+  typedef __attribute__((address_space(3))) void* lds_ptr_t;
+  const uint32_t lds_wave = (uint32_t)__builtin_amdgcn_readfirstlane(w * 8 * 128);
+  const int kc = pchunk;
 
   // ---- fragment addressing -------------------------------------------------------------
   const uint32_t fragA = (uint32_t)((wm * WTM + l32) * 128);
   const uint32_t fragB = (uint32_t)(A_BYTES + (wn * WTN + l32) * 128);
   uint32_t xo[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) xo[kk] = (uint32_t)(((kk * 2 + half) ^ (lane & 7)) << 4);
+  for (int kk = 0; kk < 4; ++kk) xo[kk] = (uint32_t)(((kk * 2 + half) ^ ((lane >> 1) & 7)) << 4);
 
   f32x16 acc[MI][NI];
 #pragma unroll
@@ -139,41 +140,72 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  auto compute = [&](int stage) {
+  u32x4 af[2][MI], bfr[2][NI];
+  // Every k-sub-step is written out as small groups "a few loads/stores + a few MFMAs",
+  // fenced so that the compiler keeps the interleaving: the matrix pipe always has work
+  // queued while LDS and global traffic for later sub-steps is in flight.
+  constexpr int NRD = MI + NI;                               // fragment reads per k-sub-step
+  constexpr int NLD = LA + LB;                               // global loads / LDS writes per k-tile
+  constexpr int NMM = MI * NI;                               // accumulator blocks
+  auto read_one = [&](int stage, int kk, int set, int r) {
     const unsigned char* sb = smem + stage * STAGE;
-    u32x4 af[2][MI], bfr[2][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i) af[0][i] = *(const u32x4*)(sb + fragA + i * 32 * 128 + xo[0]);
-#pragma unroll
-    for (int j = 0; j < NI; ++j) bfr[0][j] = *(const u32x4*)(sb + fragB + j * 32 * 128 + xo[0]);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int cur = kk & 1, nxt = cur ^ 1;
-      if (kk < 3) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) af[nxt][i] = *(const u32x4*)(sb + fragA + i * 32 * 128 + xo[kk + 1]);
-#pragma unroll
-        for (int j = 0; j < NI; ++j) bfr[nxt][j] = *(const u32x4*)(sb + fragB + j * 32 * 128 + xo[kk + 1]);
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j) mma_chunk(acc[i][j], af[cur][i], bfr[cur][j], (T*)nullptr);
-    }
+    if (r < MI) af[set][r] = *(const u32x4*)(sb + fragA + r * 32 * 128 + xo[kk]);
+    else bfr[set][r - MI] = *(const u32x4*)(sb + fragB + (r - MI) * 32 * 128 + xo[kk]);
   };
+  auto mma_one = [&](int set, int m) { mma_chunk(acc[m / NI][m % NI], af[set][m / NI], bfr[set][m % NI], (T*)nullptr); };
+  auto gload_one = [&](int kt, int stage, int i) {
+    const bool in_k = kt * BK + kc * CH < Kr;      // past the end of K every load becomes a zero fill
+    const uint32_t koff = (uint32_t)kt * 128u;
+    if (i < LA)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(smem + stage * STAGE + lds_wave + i * 32 * 128), 16,
+                                               in_k ? voffA[i] + koff : kOutOfRange, 0, 0, 0);
+    else
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)(smem + stage * STAGE + A_BYTES + lds_wave + (i - LA) * 32 * 128), 16,
+                                               in_k ? voffB[i - LA] + koff : kOutOfRange, 0, 0, 0);
+  };
+// s_waitcnt immediate: wait until at most n vector-memory operations are outstanding (other counters untouched)
+#define VMCNT(n) ((((n) & 15) | 0x0F70 | (((n) >> 4) << 14)))
+#define SLP_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-  // ---- main loop: double-buffered LDS, next tile's global loads in flight ------------
   const int nk = (Kr + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) gload_one(0, 0, i);
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) gload_one(1, 1, i);
+  __builtin_amdgcn_s_waitcnt(VMCNT(NLD));
   __syncthreads();
+#pragma unroll
+  for (int r = 0; r < NRD; ++r) read_one(0, 0, 0, r);
+  auto rd_lo = [](int g) { return 2 * g < NRD ? 2 * g : NRD; };
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) load_global(kt + 1);
-    compute(cur);
-    if (kt + 1 < nk) store_lds(cur ^ 1);
+    const int cur = kt & 1, nxt = cur ^ 1;
+#pragma unroll
+    for (int kk = 0; kk < 3; ++kk) {
+#pragma unroll
+      for (int g = 0; g < NRD; ++g) {
+#pragma unroll
+        for (int r = rd_lo(g); r < rd_lo(g + 1); ++r) read_one(cur, kk + 1, (kk + 1) & 1, r);
+#pragma unroll
+        for (int m = g * NMM / NRD; m < (g + 1) * NMM / NRD; ++m) mma_one(kk & 1, m);
+        SLP_FENCE();
+      }
+    }
+    // tile kt+1 must have landed in stage nxt (this wave's part), and every wave must be done reading stage cur
+    __builtin_amdgcn_s_waitcnt(VMCNT(0));
     __syncthreads();
+#pragma unroll
+    for (int g = 0; g < NRD; ++g) {
+#pragma unroll
+      for (int r = rd_lo(g); r < rd_lo(g + 1); ++r) read_one(nxt, 0, 0, r);
+#pragma unroll
+      for (int i = g * NLD / NRD; i < (g + 1) * NLD / NRD; ++i) gload_one(kt + 2, cur, i);
+#pragma unroll
+      for (int m = g * NMM / NRD; m < (g + 1) * NMM / NRD; ++m) mma_one(1, m);
+      SLP_FENCE();
+    }
   }
+  __builtin_amdgcn_s_waitcnt(VMCNT(0));
+#undef SLP_FENCE
 
   // ---- epilogue ----------------------------------------------------------------------------
   // Accumulator layout of the 32x32 MFMA: lane holds column n = lane & 31 and, in
@@ -234,6 +266,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
       }
     }
   }
+#endif
 }
 
 // ---- host side -------------------------------------------------------------------------------
