@@ -124,8 +124,12 @@ class Segment:
         return self.forward_all(X)[0][-1]
 
     # -- loss and its gradient w.r.t. the stored last activation -----------------
-    def loss_and_grad(self, AL, y, table=None):
-        B, D = AL.shape
+    def loss_and_grad(self, AL, y, table=None, full_batch=None):
+        """Loss and its gradient for the given rows.  ``full_batch`` is the size of
+        the batch the means run over when the rows are only a sample of it (the
+        returned loss is then these rows' share of the batch mean)."""
+        rows, D = AL.shape
+        B = rows if full_batch is None else int(full_batch)
         y = np.asarray(y, dtype=np.int64)
         if self.loss == MSE_SIL:
             T = np.asarray(table, dtype=np.float64)[y]
@@ -135,28 +139,33 @@ class Segment:
         else:
             m = AL.max(axis=1, keepdims=True)
             lse = m[:, 0] + np.log(np.sum(np.exp(AL - m), axis=1))
-            loss = float(np.sum(lse - AL[np.arange(B), y]) / B)
+            loss = float(np.sum(lse - AL[np.arange(rows), y]) / B)
             G = np.exp(AL - lse[:, None])
-            G[np.arange(B), y] -= 1.0
+            G[np.arange(rows), y] -= 1.0
             G /= B
         return loss, G
 
     # -- one training step ---------------------------------------------------------
-    def step(self, X, y, table=None, update=True):
+    def step(self, X, y, table=None, update=True, full_batch=None):
         """Forward, loss, backward, SGD.  Returns a dict with everything a
         parity test wants to look at (values *before* the update for A, Z, dZ,
-        dW, db; parameters are updated in place)."""
+        dW, db; parameters are updated in place).  With ``full_batch`` the rows
+        are a sample of a larger batch: A, Z and dZ of those rows are exact (they
+        depend on the rest of the batch only through its size); loss is then these
+        rows' share, dW and db are not formed and no update may be asked for."""
+        assert full_batch is None or not update
         Wp = self._weights_for_products()
         A, Z = self.forward_all(X)
-        loss, G = self.loss_and_grad(A[self.L], y, table)
+        loss, G = self.loss_and_grad(A[self.L], y, table, full_batch)
         dZ = [None] * (self.L + 1)
         dW = [None] * self.L
         db = [None] * self.L
         g = G * (A[self.L] > 0.0) if self._relu_on(self.L) else G
         dZ[self.L] = self._store(g)
         for l in range(self.L, 0, -1):
-            dW[l - 1] = dZ[l].T @ A[l - 1]
-            db[l - 1] = dZ[l].sum(axis=0)
+            if full_batch is None:       # parameter gradients need every row of the batch
+                dW[l - 1] = dZ[l].T @ A[l - 1]
+                db[l - 1] = dZ[l].sum(axis=0)
             if l > 1:
                 dA = dZ[l] @ Wp[l - 1]
                 dZ[l - 1] = self._store(dA * (A[l - 1] > 0.0))

@@ -167,39 +167,61 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dZ
 // ---------------------------------------------------------------------------------
 // SGD with momentum on one weight matrix + derived copies
 // ---------------------------------------------------------------------------------
+// A block owns a 64 (out) x 64 (in) tile.  Every thread moves 16-byte vectors: four
+// consecutive inputs of one output row for the float32 streams (gradient, momentum,
+// master weight), and four consecutive outputs of one input row for the transposed copy,
+// which goes through an LDS tile.  Pad columns (in >= K, up to the leading dimension) hold
+// zeros in all three streams and stay zero under the update, so the row direction needs
+// no tail handling.
 template <typename T>
 __global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32, float* __restrict__ vW,
                                                          const float* __restrict__ dW, int N, int K, int ldk,
                                                          bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
                                                          float mu, int refresh_only) {
-  __shared__ T tile[64][65];
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  typedef T tx4 __attribute__((ext_vector_type(4)));
+  typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  __shared__ T tile[64][68];
   const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int rr = ty; rr < 64; rr += 4) {
-    const int n = n0 + rr, k = k0 + tx;
-    T wv = from_f32<T>(0.0f);
+  const int q = threadIdx.x & 15, r = threadIdx.x >> 4;
+  const int k = k0 + q * 4;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int rr = r + 16 * p, n = n0 + rr;
+    f32x4 w = {0.0f, 0.0f, 0.0f, 0.0f};
     if (n < N && k < K) {
       const size_t idx = (size_t)n * ldk + k;
-      float w = W32[idx];
+      w = *(const f32x4*)(W32 + idx);
       if (!refresh_only) {
-        float v = dW[idx];
+        f32x4 v = *(const f32x4*)(dW + idx);
         if (mu != 0.0f) {
-          v = mu * vW[idx] + v;
-          vW[idx] = v;
+          v = mu * *(const f32x4*)(vW + idx) + v;
+          *(f32x4*)(vW + idx) = v;
         }
         w = w - lr * v;
-        W32[idx] = w;
+        *(f32x4*)(W32 + idx) = w;
       }
-      wv = from_f32<T>(w);
-      if (W16) W16[idx] = (bf16)w;
+      if (W16) {
+        bf16x4 h;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = (bf16)w[e];
+        *(bf16x4*)(W16 + idx) = h;
+      }
     }
-    tile[rr][tx] = wv;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) tile[rr][q * 4 + e] = from_f32<T>(w[e]);
   }
   if (!WT) return;
   __syncthreads();
-  for (int kk = ty; kk < 64; kk += 4) {
-    const int k = k0 + kk, n = n0 + tx;
-    if (k < K && n < N) WT[(size_t)k * ldn + n] = tile[tx][kk];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int kk = r + 16 * p, kg = k0 + kk, n = n0 + q * 4;
+    if (kg < K && n < N) {
+      tx4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = tile[q * 4 + e][kk];
+      *(tx4*)(WT + (size_t)kg * ldn + n) = o;
+    }
   }
 }
 

@@ -1,0 +1,99 @@
+"""The comparison configuration at its real shape and in the launch configuration
+the benchmark times (784-16384-16384-16384, bf16, batch 8192, 256x256 tiles).
+
+A full oracle step at this size is ~27 TFLOP of float64 work, so:
+  * sampled batch rows are pushed through the oracle's whole forward and backward
+    chain (a row of A_l / dZ_l depends on the other rows only through the batch
+    size in the means) and compared element by element;
+  * what needs every row (loss, dW, db, the update) is checked through properties
+    that hold at any size: the loss against its definition on the device's own
+    output, dW and db against random projections / column sums of the device's own
+    dZ and A (float64 on the host), the update against w - lr * dW.
+"""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rng as orng
+from oracle import segment as osg
+from paper_2403_11204_amd import api, datagen
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+TOL = 2e-2
+DEV = "cuda"
+
+
+def f64(t):
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def test_comparison_config_segment_a_full_size():
+    widths, B, classes, lr = [784, 16384, 16384, 16384], 8192, 1000, 0.01
+    X, y = datagen.class_mean_inputs(B, classes, dim=784, seed=1)
+    table = orng.make_synthetic_labels(31, classes, widths[-1], orng.UNIFORM_PM1)
+    params = datagen.uniform_weights(widths, seed=17)
+
+    seg = api.Segment(widths, api.RELU_ALL, api.MSE_SIL, max_batch=B, dtype=api.BF16, lr=lr, momentum=0.9)
+    for l, (W, b) in enumerate(params):
+        seg.set_params(l, torch.from_numpy(W), torch.from_numpy(b))
+    seg.set_labels(torch.from_numpy(table).to(DEV))
+    Xd = torch.from_numpy(X).to(DEV).to(torch.bfloat16).contiguous()
+    yd = torch.from_numpy(y).to(DEV)
+    loss_gpu = float(seg.step(Xd, yd).item())
+    print("full-size step done, loss", loss_gpu, flush=True)
+
+    # ---- sampled rows through the oracle chain ---------------------------------------
+    rows = np.array([0, 1, 4097, 8191])
+    ora = osg.Segment(widths, osg.RELU_ALL, osg.MSE_SIL, lr=lr, momentum=0.9, mode="bf16")
+    for l, (W, b) in enumerate(params):
+        ora.set_params(l, W, b)
+    Xrows = f64(Xd[torch.from_numpy(rows).to(DEV)])
+    out = ora.step(Xrows, y[rows], table, update=False, full_batch=B)
+    print("oracle rows done", flush=True)
+    ridx = torch.from_numpy(rows).to(DEV)
+    flipped = np.zeros(len(rows), dtype=bool)
+    for l in range(3, 0, -1):
+        a_got = f64(seg.get_activation(l, B)[ridx])
+        a_ref = out["A"][l]
+        assert np.max(np.abs(a_got - a_ref)) <= TOL * np.max(np.abs(a_ref)), ("A", l)
+        mism = (a_got > 0) != (a_ref > 0)
+        if mism.any():       # only near-ties of the oracle's pre-activation may be decided differently
+            assert np.all(np.abs(out["Z"][l][mism]) <= 1e-3 * np.max(np.abs(out["Z"][l]))), ("mask", l)
+            assert mism.mean() <= 1e-3
+            flipped |= mism.any(axis=1)
+        dz_got = f64(seg.get_activation(l, B, kind=1)[ridx])
+        dz_ref = out["dZ"][l]
+        assert np.linalg.norm(dz_got - dz_ref) <= TOL * np.linalg.norm(dz_ref), ("dZ L2", l)
+        keep = ~flipped
+        if keep.any():
+            assert np.max(np.abs(dz_got[keep] - dz_ref[keep])) <= TOL * np.max(np.abs(dz_ref)), ("dZ", l)
+    del ora, out
+
+    # ---- properties over the whole batch ---------------------------------------------------
+    A = [None] + [seg.get_activation(l, B) for l in (1, 2, 3)]
+    A[0] = Xd
+    dZ = [None] + [seg.get_activation(l, B, kind=1) for l in (1, 2, 3)]
+    T = torch.from_numpy(table).to(DEV)[yd.long()]
+    diff = A[3].double() - T.double()
+    loss_def = float((diff * diff).mean().item())          # definition of the loss on the device's own output
+    assert abs(loss_gpu - loss_def) <= 1e-5 * loss_def
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    for l in range(3):
+        dW, db = seg.get_grads(l)
+        r = torch.randn(widths[l], generator=gen, dtype=torch.float64).to(DEV)
+        # dW r = dZ^T (A r): a wrong tile, a dropped k-slice or a transposed operand breaks this
+        lhs = dW.double() @ r
+        rhs = dZ[l + 1].double().T @ (A[l].double() @ r)
+        assert float((lhs - rhs).abs().max() / rhs.abs().max()) <= 1e-4, ("dW", l)
+        col = dZ[l + 1].double().sum(dim=0)
+        assert float((db.double() - col).abs().max() / col.abs().max()) <= 1e-4, ("db", l)
+        # first step from zero momentum: v = dW, w_new = w_old - lr * dW (float32 arithmetic)
+        Wn, bn = seg.get_params(l)
+        W0 = torch.from_numpy(params[l][0]).to(DEV)
+        expect = W0 - lr * dW
+        assert float((Wn - expect).abs().max()) <= 2 * float(np.spacing(np.float32(W0.abs().max().item()))), ("W", l)
+        vW, _ = seg.get_momentum(l)
+        assert torch.equal(vW, dW)
+        del dW, Wn, W0, expect, vW

@@ -337,3 +337,21 @@ def test_bf16_mode_rounds_at_storage_points_only():
     assert np.allclose(ob["dW"][1], ob["dZ"][2].T @ ob["A"][1], rtol=1e-14)
     assert not np.array_equal(ob["dW"][1], rng.round_to_bf16(ob["dW"][1].astype(np.float32)))
     assert np.max(np.abs(ob["dW"][1] - oa["dW"][1])) <= 0.05 * np.max(np.abs(oa["dW"][1]))
+
+
+def test_sampled_rows_of_a_larger_batch():
+    # A, Z and dZ of a row depend on the other rows only through the batch size in the means
+    widths = [9, 11, 7]
+    g = np.random.default_rng(21)
+    X = g.uniform(0, 1, (12, 9))
+    y = g.integers(0, 4, 12)
+    T = g.standard_normal((4, 7))
+    for act, loss in ((osg.RELU_ALL, osg.MSE_SIL), (osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT)):
+        seg = _rand_segment(widths, act, loss, seed=2)
+        full = seg.step(X, y, T, update=False)
+        rows = np.array([0, 5, 11])
+        part = seg.step(X[rows], y[rows], T, update=False, full_batch=12)
+        for l in (1, 2):
+            assert np.array_equal(part["A"][l], full["A"][l][rows])
+            assert np.allclose(part["dZ"][l], full["dZ"][l][rows], rtol=1e-13, atol=0)
+        assert part["dW"][0] is None
