@@ -168,6 +168,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-e2e", action="store_true", help="skip the end-to-end backprop comparison (config 4)")
     ap.add_argument("--cpu-rows", type=int, default=None)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="first run one plain 1 GiB -> 1 GiB elementwise copy kernel (scale reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (segments are independent jobs; no collectives exist): use --gpus 1")
@@ -179,6 +181,13 @@ def main():
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
     dt, B = cfg["dtype"], cfg["batch"]
 
+    if args.calib_copy:
+        src = torch.rand(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)                                         # one kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     torch.cuda.reset_peak_memory_stats()
     segs, inputs, ys = build_segments(cfg, n_batches=2 if big else 8)
     torch.cuda.synchronize()
