@@ -185,31 +185,42 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32
   const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
   const int q = threadIdx.x & 15, r = threadIdx.x >> 4;
   const int k = k0 + q * 4;
+  // all loads of the thread's four rows are issued before the first store, so that 9 to 12
+  // 16-byte requests per thread are in flight
+  f32x4 w[4], gr[4], vo[4];
+  const bool with_v = !refresh_only && mu != 0.0f;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int n = n0 + r + 16 * p;
+    const bool in = n < N && k < K;
+    const size_t idx = (size_t)n * ldk + k;
+    w[p] = in ? __builtin_nontemporal_load((const f32x4*)(W32 + idx)) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    gr[p] = (in && !refresh_only) ? __builtin_nontemporal_load((const f32x4*)(dW + idx)) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    vo[p] = (in && with_v) ? __builtin_nontemporal_load((const f32x4*)(vW + idx)) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  }
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int rr = r + 16 * p, n = n0 + rr;
-    f32x4 w = {0.0f, 0.0f, 0.0f, 0.0f};
     if (n < N && k < K) {
       const size_t idx = (size_t)n * ldk + k;
-      w = *(const f32x4*)(W32 + idx);
       if (!refresh_only) {
-        f32x4 v = *(const f32x4*)(dW + idx);
-        if (mu != 0.0f) {
-          v = mu * *(const f32x4*)(vW + idx) + v;
-          *(f32x4*)(vW + idx) = v;
+        f32x4 v = gr[p];
+        if (with_v) {
+          v = mu * vo[p] + v;
+          __builtin_nontemporal_store(v, (f32x4*)(vW + idx));
         }
-        w = w - lr * v;
-        *(f32x4*)(W32 + idx) = w;
+        w[p] = w[p] - lr * v;
+        __builtin_nontemporal_store(w[p], (f32x4*)(W32 + idx));
       }
       if (W16) {
         bf16x4 h;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = (bf16)w[e];
+        for (int e = 0; e < 4; ++e) h[e] = (bf16)w[p][e];
         *(bf16x4*)(W16 + idx) = h;
       }
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) tile[rr][q * 4 + e] = from_f32<T>(w[e]);
+    for (int e = 0; e < 4; ++e) tile[rr][q * 4 + e] = from_f32<T>(w[p][e]);
   }
   if (!WT) return;
   __syncthreads();
