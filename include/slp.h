@@ -59,6 +59,8 @@ typedef struct {
   int max_batch;  /* largest batch a step or forward call may pass */
   float lr;       /* SGD learning rate (Sec. 3 uses 0.01) */
   float momentum; /* SGD momentum (Sec. 3 uses 0.9); 0 = plain SGD */
+  int input_grad; /* 1: the segment can also return d loss / d input (slp_segment_input_grad); costs a
+                     transposed copy of the first layer's weights and one input-sized buffer */
 } slp_opts;
 
 const char* slp_last_error(void);
@@ -142,6 +144,22 @@ int slp_segment_step(slp_segment* seg, const void* X /*device*/, const int32_t* 
  * partitions): out[batch][last width], dense, handle dtype, device.  Parameters
  * are not changed; the activation workspace is overwritten. */
 int slp_segment_forward(slp_segment* seg, const void* X /*device*/, int batch, void* out /*device*/, slp_stream stream);
+
+/* ---- recovery phase (Sec. 5: the left partition is trained some more while the
+ * right partition's weights are frozen) ------------------------------------------------
+ * slp_segment_input_grad runs forward, the segment's own loss against `targets` and
+ * the data gradients of EVERY layer, and writes d loss / d X to dX[batch][widths[0]]
+ * (dense, handle dtype, device).  No parameter, momentum or gradient buffer changes:
+ * this is the frozen partition.  Needs opts.input_grad = 1 (else SLP_ERR_STATE).
+ * slp_segment_step_external is a training step whose output gradient comes from
+ * outside: dA_out[batch][last width] (dense, handle dtype, device) = d loss / d (segment
+ * output).  dZ_L = dA_out where the last layer's ReLU is active (or everywhere on an
+ * identity-last segment), then the usual backward pass and SGD update.  Chaining
+ * left.forward -> right.input_grad -> left.step_external is one recovery step. */
+int slp_segment_input_grad(slp_segment* seg, const void* X /*device*/, const int32_t* targets /*device*/, int batch,
+                           void* dX /*device*/, float* loss_out /*device, may be NULL*/, slp_stream stream);
+int slp_segment_step_external(slp_segment* seg, const void* X /*device*/, const void* dA_out /*device*/, int batch,
+                              slp_stream stream);
 
 /* ---- measurement hooks -------------------------------------------------------------
  * When enabled, every matrix-product launch of the segment is bracketed by HIP

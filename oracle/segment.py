@@ -179,3 +179,56 @@ class Segment:
                     self.W[l] = self.W[l].astype(np.float32).astype(np.float64)
                     self.b[l] = self.b[l].astype(np.float32).astype(np.float64)
         return {"loss": loss, "A": A, "Z": Z, "dZ": dZ, "dW": dW, "db": db}
+
+
+# -- recovery phase (paper Sec. 5) ---------------------------------------------------
+# After both partitions are trained, the left one is trained some more *through* the
+# right one, whose weights stay frozen: the loss is the right partition's
+# classification loss on the left partition's response.  That needs two more
+# operations, added to the class below: the gradient of a segment's loss with
+# respect to its INPUT (no parameter gradient, no update), and a training step that
+# starts from a gradient handed in from outside instead of from the segment's own loss.
+def _input_gradient(self, X, y, table=None):
+    """Forward, loss, and backpropagation through every layer down to the input.
+    Parameters are not touched.  Returns {"loss", "dX", "A", "Z", "dZ"}; dX is
+    d loss / d X (rounded to bf16 in bf16 mode, like every stored gradient)."""
+    Wp = self._weights_for_products()
+    A, Z = self.forward_all(X)
+    loss, G = self.loss_and_grad(A[self.L], y, table)
+    dZ = [None] * (self.L + 1)
+    dZ[self.L] = self._store(G * (A[self.L] > 0.0) if self._relu_on(self.L) else G)
+    for l in range(self.L, 1, -1):
+        dZ[l - 1] = self._store((dZ[l] @ Wp[l - 1]) * (A[l - 1] > 0.0))
+    dX = self._store(dZ[1] @ Wp[0])          # the input is not a ReLU output of this segment: no mask
+    return {"loss": loss, "dX": dX, "A": A, "Z": Z, "dZ": dZ}
+
+
+def _step_external(self, X, dA_out, update=True):
+    """A training step driven by dA_out = d loss / d (segment output), supplied by
+    whatever sits behind the segment.  dZ_L = dA_out * [A_L > 0] when the last
+    layer has a ReLU, else dA_out; then the usual backward pass and SGD update."""
+    Wp = self._weights_for_products()
+    A, Z = self.forward_all(X)
+    g = self._store(np.asarray(dA_out, dtype=np.float64))
+    dZ = [None] * (self.L + 1)
+    dZ[self.L] = self._store(g * (A[self.L] > 0.0)) if self._relu_on(self.L) else g
+    dW, db = [None] * self.L, [None] * self.L
+    for l in range(self.L, 0, -1):
+        dW[l - 1] = dZ[l].T @ A[l - 1]
+        db[l - 1] = dZ[l].sum(axis=0)
+        if l > 1:
+            dZ[l - 1] = self._store((dZ[l] @ Wp[l - 1]) * (A[l - 1] > 0.0))
+    if update:
+        for l in range(self.L):
+            self.vW[l] = self.mu * self.vW[l] + dW[l]
+            self.vb[l] = self.mu * self.vb[l] + db[l]
+            self.W[l] = self.W[l] - self.lr * self.vW[l]
+            self.b[l] = self.b[l] - self.lr * self.vb[l]
+            if self.mode == "bf16":
+                self.W[l] = self.W[l].astype(np.float32).astype(np.float64)
+                self.b[l] = self.b[l].astype(np.float32).astype(np.float64)
+    return {"A": A, "Z": Z, "dZ": dZ, "dW": dW, "db": db}
+
+
+Segment.input_gradient = _input_gradient
+Segment.step_external = _step_external

@@ -27,7 +27,8 @@ class SlpError(RuntimeError):
 
 
 class _Opts(ctypes.Structure):
-    _fields_ = [("dtype", ctypes.c_int), ("max_batch", ctypes.c_int), ("lr", ctypes.c_float), ("momentum", ctypes.c_float)]
+    _fields_ = [("dtype", ctypes.c_int), ("max_batch", ctypes.c_int), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
+                ("input_grad", ctypes.c_int)]
 
 
 def lib():
@@ -59,6 +60,8 @@ def lib():
         "slp_segment_set_labels": (i32, [vp, vp, i32, i32]),
         "slp_segment_step": (i32, [vp, vp, vp, i32, vp, vp]),
         "slp_segment_forward": (i32, [vp, vp, i32, vp, vp]),
+        "slp_segment_input_grad": (i32, [vp, vp, vp, i32, vp, vp, vp]),
+        "slp_segment_step_external": (i32, [vp, vp, vp, i32, vp]),
         "slp_segment_profile_enable": (i32, [vp, i32]),
         "slp_segment_profile_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]),
     }
@@ -73,7 +76,8 @@ EXPORTS = ["slp_last_error", "slp_make_synthetic_labels", "slp_make_segment_inpu
            "slp_segment_destroy", "slp_segment_param_bytes", "slp_segment_workspace_bytes", "slp_segment_bind",
            "slp_segment_init", "slp_segment_set_params", "slp_segment_get_params", "slp_segment_get_grads",
            "slp_segment_get_momentum", "slp_segment_get_activation", "slp_segment_set_lr", "slp_segment_set_labels",
-           "slp_segment_step", "slp_segment_forward", "slp_segment_profile_enable", "slp_segment_profile_read"]
+           "slp_segment_step", "slp_segment_forward", "slp_segment_input_grad", "slp_segment_step_external",
+           "slp_segment_profile_enable", "slp_segment_profile_read"]
 
 
 def _check(code):
@@ -112,12 +116,12 @@ def make_segment_inputs(seed, table, y, first_sample, sigma, dtype=F32):
 class Segment:
     """One network segment: owns the handle and the two torch buffers bound to it."""
 
-    def __init__(self, widths, act, loss, max_batch, dtype=F32, lr=0.01, momentum=0.9, device="cuda"):
+    def __init__(self, widths, act, loss, max_batch, dtype=F32, lr=0.01, momentum=0.9, input_grad=False, device="cuda"):
         self.widths, self.act, self.loss, self.dtype, self.max_batch = list(widths), act, loss, dtype, max_batch
         self.L = len(widths) - 1
         self.device = torch.device(device)
         arr = (ctypes.c_int * len(widths))(*widths)
-        opts = _Opts(dtype, max_batch, lr, momentum)
+        opts = _Opts(dtype, max_batch, lr, momentum, int(input_grad))
         h = ctypes.c_void_p()
         self._h = None
         _check(lib().slp_segment_create(arr, len(widths), act, loss, ctypes.byref(opts), ctypes.byref(h)))
@@ -186,6 +190,20 @@ class Segment:
             out = torch.empty((X.shape[0], self.widths[-1]), dtype=X.dtype, device=X.device)
         _check(lib().slp_segment_forward(self._h, _ptr(X), X.shape[0], _ptr(out), _stream()))
         return out
+
+    def input_grad(self, X, targets):
+        """slp_segment_input_grad: (d loss / d X, device scalar loss); parameters untouched."""
+        assert X.is_cuda and X.is_contiguous() and X.dtype == _torch_dtype(self.dtype) and X.shape[1] == self.widths[0]
+        assert targets.dtype == torch.int32 and targets.numel() == X.shape[0]
+        dX = torch.empty_like(X)
+        _check(lib().slp_segment_input_grad(self._h, _ptr(X), _ptr(targets), X.shape[0], _ptr(dX), _ptr(self._loss), _stream()))
+        return dX, self._loss
+
+    def step_external(self, X, dA_out):
+        """slp_segment_step_external: training step from a gradient w.r.t. the segment output."""
+        assert X.is_cuda and X.is_contiguous() and X.dtype == _torch_dtype(self.dtype) and X.shape[1] == self.widths[0]
+        assert dA_out.is_contiguous() and dA_out.dtype == X.dtype and tuple(dA_out.shape) == (X.shape[0], self.widths[-1])
+        _check(lib().slp_segment_step_external(self._h, _ptr(X), _ptr(dA_out), X.shape[0], _stream()))
 
     def profile_enable(self, on=True):
         _check(lib().slp_segment_profile_enable(self._h, int(on)))

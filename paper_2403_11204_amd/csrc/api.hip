@@ -66,6 +66,7 @@ struct slp_segment {
   int n_partials;
   float *partials, *loss_dev;
   bool bound, have_params;
+  bool input_grad;                           // keeps W_1^T and a dZ_0 buffer so that d loss / d input can be formed
   const float* table;
   int classes;
   int last_batch;
@@ -117,7 +118,7 @@ int check_seg(const slp_segment* s, bool need_bound, bool need_params) {
 // X[batch][w0] -> A[0] (padded rows) and, for training, its transpose
 int ingest(slp_segment* s, const void* X, int batch, bool with_transpose, hipStream_t st) {
   HIP_TRY(launch_copy_transpose(s->dtype, X, s->widths[0], batch, s->widths[0], s->A[0], s->ldw[0],
-                                with_transpose ? s->AT[0] : nullptr, s->ldb, 1, st));
+                                with_transpose ? s->AT[0] : nullptr, s->ldb, 1, nullptr, 0, st));
   return SLP_OK;
 }
 
@@ -133,6 +134,58 @@ int forward_layers(slp_segment* s, int batch, bool training, hipStream_t st) {
     g.bias = ly.b; g.relu = relu_on(s, l) ? 1 : 0;
     int rc = run_gemm(s, EPI_FWD, g, st);
     if (rc) return rc;
+  }
+  return SLP_OK;
+}
+
+// loss and dZ_L (row-major for the data gradient, transposed for the weight gradient)
+int loss_and_output_grad(slp_segment* seg, const int32_t* targets, int batch, float* loss_out, hipStream_t st) {
+  const int L = seg->L, D = seg->widths[L];
+  if (seg->loss == SLP_MSE_SIL) {
+    HIP_TRY(launch_mse_loss_grad(seg->dtype, seg->A[L], seg->ldw[L], targets, seg->table, seg->classes, batch, D,
+                                 relu_on(seg, L) ? 1 : 0, seg->dZ[L], seg->dZT[L], seg->ldb, seg->partials, st));
+    HIP_TRY(launch_reduce_loss(seg->partials, mse_partial_count(batch, D), 1.0 / ((double)batch * D), seg->loss_dev, loss_out, st));
+  } else {
+    HIP_TRY(launch_xent_loss_grad(seg->dtype, seg->A[L], seg->ldw[L], targets, batch, D, relu_on(seg, L) ? 1 : 0,
+                                  seg->dZ[L], seg->partials, st));
+    HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZ[L], seg->ldw[L], batch, D, nullptr, 0, seg->dZT[L], seg->ldb, 1,
+                                  nullptr, 0, st));
+    HIP_TRY(launch_reduce_loss(seg->partials, batch, 1.0 / (double)batch, seg->loss_dev, loss_out, st));
+  }
+  return SLP_OK;
+}
+
+// dZ_{l-1} = (dZ_l W_l) * [A_{l-1} > 0]; for l = 1 the result is the gradient w.r.t. the segment input (no mask)
+int data_gradient(slp_segment* seg, int l, int batch, hipStream_t st) {
+  Layer& ly = seg->layers[l - 1];
+  GemmArgs g{};
+  g.A = seg->dZ[l]; g.lda = seg->ldw[l];
+  g.B = ly.WT;      g.ldb = ly.ldn;
+  g.M = batch; g.N = ly.K; g.K = ly.N;
+  g.C = seg->dZ[l - 1]; g.ldc = seg->ldw[l - 1];
+  g.CT = l > 1 ? seg->dZT[l - 1] : nullptr; g.ldct = seg->ldb;
+  g.maskT = l > 1 ? seg->AT[l - 1] : nullptr; g.ldmask = seg->ldb;
+  return run_gemm(seg, EPI_DGRAD, g, st);
+}
+
+// backward + update, last layer first; the data gradient of layer l reads W_l before it is updated
+int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
+  for (int l = seg->L; l >= 1; --l) {
+    Layer& ly = seg->layers[l - 1];
+    if (l > 1) {
+      int rc = data_gradient(seg, l, batch, st);
+      if (rc) return rc;
+    }
+    GemmArgs g{};
+    g.A = seg->dZT[l];    g.lda = seg->ldb;
+    g.B = seg->AT[l - 1]; g.ldb = seg->ldb;
+    g.M = ly.N; g.N = ly.K; g.K = batch;
+    g.Cf = ly.dW; g.ldc = ly.ldk;
+    int rc = run_gemm(seg, EPI_WGRAD, g, st);
+    if (rc) return rc;
+    HIP_TRY(launch_bias_grad(seg->dtype, seg->dZT[l], seg->ldb, ly.N, batch, ly.db, st));
+    HIP_TRY(launch_sgd_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->lr, seg->mu, 0, st));
+    HIP_TRY(launch_bias_update(ly.b, ly.vb, ly.db, ly.N, seg->lr, seg->mu, st));
   }
   return SLP_OK;
 }
@@ -221,6 +274,7 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
   s->L = n_widths - 1; s->act = act; s->loss = loss; s->dtype = opts->dtype; s->max_batch = opts->max_batch;
   s->ldb = round_up(opts->max_batch, kLdAlign);
   s->lr = opts->lr; s->mu = opts->momentum;
+  s->input_grad = opts->input_grad != 0;
   s->widths.assign(widths, widths + n_widths);
   for (int w : s->widths) s->ldw.push_back(round_up(w, kLdAlign));
   const size_t es = esize(s);
@@ -248,7 +302,7 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
     ly.oW32 = take(wbytes); ly.ovW = take(wbytes); ly.odW = take(wbytes);
     ly.ob = take((size_t)ly.N * 4); ly.ovb = take((size_t)ly.N * 4); ly.odb = take((size_t)ly.N * 4);
     ly.oW16 = s->dtype == SLP_BF16 ? take((size_t)ly.N * ly.ldk * 2) : (size_t)-1;
-    ly.oWT = l > 0 ? take((size_t)ly.K * ly.ldn * es) : (size_t)-1;
+    ly.oWT = (l > 0 || s->input_grad) ? take((size_t)ly.K * ly.ldn * es) : (size_t)-1;
     s->layers.push_back(ly);
   }
   s->param_bytes = off;
@@ -258,8 +312,11 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
   for (int l = 0; l <= s->L; ++l) {
     s->oA[l] = take((size_t)s->max_batch * s->ldw[l] * es);
     if (l < s->L) s->oAT[l] = take((size_t)s->widths[l] * s->ldb * es);
+    if (l == 0 && s->input_grad) s->odZ[0] = take((size_t)s->max_batch * s->ldw[0] * es);
     if (l >= 1) {
-      if (l >= 2 || l == s->L) s->odZ[l] = take((size_t)s->max_batch * s->ldw[l] * es);
+      // row-major dZ_l is the A operand of layer l's data gradient: needed for l >= 2, for the loss
+      // kernels' output (l = L), and for l = 1 when the gradient w.r.t. the input is wanted
+      if (l >= 2 || l == s->L || s->input_grad) s->odZ[l] = take((size_t)s->max_batch * s->ldw[l] * es);
       s->odZT[l] = take((size_t)s->widths[l] * s->ldb * es);
     }
   }
@@ -357,13 +414,13 @@ int slp_segment_get_activation(slp_segment* seg, int layer, int kind, int batch,
   hipStream_t st = (hipStream_t)stream;
   const int w = seg->widths[layer];
   if (kind == 0) {
-    HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[layer], seg->ldw[layer], batch, w, out, w, nullptr, 0, 0, st));
+    HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[layer], seg->ldw[layer], batch, w, out, w, nullptr, 0, 0, nullptr, 0, st));
   } else {
     if (layer < 1) return fail(SLP_ERR_ARG, "no gradient is formed for the segment input");
     if (seg->dZ[layer]) {
-      HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZ[layer], seg->ldw[layer], batch, w, out, w, nullptr, 0, 0, st));
+      HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZ[layer], seg->ldw[layer], batch, w, out, w, nullptr, 0, 0, nullptr, 0, st));
     } else {   // only the transposed copy exists: transpose it back
-      HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZT[layer], seg->ldb, w, batch, nullptr, 0, out, w, 0, st));
+      HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZT[layer], seg->ldb, w, batch, nullptr, 0, out, w, 0, nullptr, 0, st));
     }
   }
   return SLP_OK;
@@ -398,7 +455,7 @@ int slp_segment_forward(slp_segment* seg, const void* X, int batch, void* out, s
   rc = forward_layers(seg, batch, false, st);
   if (rc) return rc;
   const int w = seg->widths[seg->L];
-  HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[seg->L], seg->ldw[seg->L], batch, w, out, w, nullptr, 0, 0, st));
+  HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[seg->L], seg->ldw[seg->L], batch, w, out, w, nullptr, 0, 0, nullptr, 0, st));
   seg->last_batch = batch;
   return SLP_OK;
 }
@@ -410,52 +467,60 @@ int slp_segment_step(slp_segment* seg, const void* X, const int32_t* targets, in
   if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
   if (seg->loss == SLP_MSE_SIL && !seg->table) return fail(SLP_ERR_STATE, "no label table bound: call slp_segment_set_labels first");
   hipStream_t st = (hipStream_t)stream;
-  const int L = seg->L, D = seg->widths[L];
 
   rc = ingest(seg, X, batch, true, st);
   if (rc) return rc;
   rc = forward_layers(seg, batch, true, st);
   if (rc) return rc;
+  rc = loss_and_output_grad(seg, targets, batch, loss_out, st);
+  if (rc) return rc;
+  rc = backward_and_update(seg, batch, st);
+  if (rc) return rc;
+  seg->last_batch = batch;
+  return SLP_OK;
+}
 
-  // loss and dZ_L (row-major for the data gradient, transposed for the weight gradient)
-  if (seg->loss == SLP_MSE_SIL) {
-    HIP_TRY(launch_mse_loss_grad(seg->dtype, seg->A[L], seg->ldw[L], targets, seg->table, seg->classes, batch, D,
-                                 relu_on(seg, L) ? 1 : 0, seg->dZ[L], seg->dZT[L], seg->ldb, seg->partials, st));
-    HIP_TRY(launch_reduce_loss(seg->partials, mse_partial_count(batch, D), 1.0 / ((double)batch * D), seg->loss_dev, loss_out, st));
-  } else {
-    HIP_TRY(launch_xent_loss_grad(seg->dtype, seg->A[L], seg->ldw[L], targets, batch, D, relu_on(seg, L) ? 1 : 0,
-                                  seg->dZ[L], seg->partials, st));
-    HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZ[L], seg->ldw[L], batch, D, nullptr, 0, seg->dZT[L], seg->ldb, 1, st));
-    HIP_TRY(launch_reduce_loss(seg->partials, batch, 1.0 / (double)batch, seg->loss_dev, loss_out, st));
+int slp_segment_input_grad(slp_segment* seg, const void* X, const int32_t* targets, int batch, void* dX, float* loss_out,
+                           slp_stream stream) {
+  int rc = check_seg(seg, true, true);
+  if (rc) return rc;
+  if (!seg->input_grad) return fail(SLP_ERR_STATE, "segment was created without input_grad");
+  if (!X || !targets || !dX) return fail(SLP_ERR_ARG, "X, targets and dX must not be NULL");
+  if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
+  if (seg->loss == SLP_MSE_SIL && !seg->table) return fail(SLP_ERR_STATE, "no label table bound: call slp_segment_set_labels first");
+  hipStream_t st = (hipStream_t)stream;
+  rc = ingest(seg, X, batch, true, st);
+  if (rc) return rc;
+  rc = forward_layers(seg, batch, true, st);
+  if (rc) return rc;
+  rc = loss_and_output_grad(seg, targets, batch, loss_out, st);
+  if (rc) return rc;
+  for (int l = seg->L; l >= 1; --l) {       // data gradients only, down to the input; parameters untouched
+    rc = data_gradient(seg, l, batch, st);
+    if (rc) return rc;
   }
+  const int w0 = seg->widths[0];
+  HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZ[0], seg->ldw[0], batch, w0, dX, w0, nullptr, 0, 0, nullptr, 0, st));
+  seg->last_batch = batch;
+  return SLP_OK;
+}
 
-  // backward + update, last layer first; the data gradient of layer l reads W_l before it is updated
-  for (int l = L; l >= 1; --l) {
-    Layer& ly = seg->layers[l - 1];
-    if (l > 1) {
-      GemmArgs g{};
-      g.A = seg->dZ[l]; g.lda = seg->ldw[l];
-      g.B = ly.WT;      g.ldb = ly.ldn;
-      g.M = batch; g.N = ly.K; g.K = ly.N;
-      g.C = seg->dZ[l - 1]; g.ldc = seg->ldw[l - 1];
-      g.CT = seg->dZT[l - 1]; g.ldct = seg->ldb;
-      g.maskT = seg->AT[l - 1]; g.ldmask = seg->ldb;
-      rc = run_gemm(seg, EPI_DGRAD, g, st);
-      if (rc) return rc;
-    }
-    {
-      GemmArgs g{};
-      g.A = seg->dZT[l];    g.lda = seg->ldb;
-      g.B = seg->AT[l - 1]; g.ldb = seg->ldb;
-      g.M = ly.N; g.N = ly.K; g.K = batch;
-      g.Cf = ly.dW; g.ldc = ly.ldk;
-      rc = run_gemm(seg, EPI_WGRAD, g, st);
-      if (rc) return rc;
-    }
-    HIP_TRY(launch_bias_grad(seg->dtype, seg->dZT[l], seg->ldb, ly.N, batch, ly.db, st));
-    HIP_TRY(launch_sgd_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->lr, seg->mu, 0, st));
-    HIP_TRY(launch_bias_update(ly.b, ly.vb, ly.db, ly.N, seg->lr, seg->mu, st));
-  }
+int slp_segment_step_external(slp_segment* seg, const void* X, const void* dA_out, int batch, slp_stream stream) {
+  int rc = check_seg(seg, true, true);
+  if (rc) return rc;
+  if (!X || !dA_out) return fail(SLP_ERR_ARG, "X and dA_out must not be NULL");
+  if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
+  hipStream_t st = (hipStream_t)stream;
+  const int L = seg->L, D = seg->widths[L];
+  rc = ingest(seg, X, batch, true, st);
+  if (rc) return rc;
+  rc = forward_layers(seg, batch, true, st);
+  if (rc) return rc;
+  // dZ_L = dA_out * [A_L > 0] (ReLU on the last layer) or dA_out, in both layouts
+  HIP_TRY(launch_copy_transpose(seg->dtype, dA_out, D, batch, D, seg->dZ[L], seg->ldw[L], seg->dZT[L], seg->ldb, 1,
+                                relu_on(seg, L) ? seg->A[L] : nullptr, seg->ldw[L], st));
+  rc = backward_and_update(seg, batch, st);
+  if (rc) return rc;
   seg->last_batch = batch;
   return SLP_OK;
 }

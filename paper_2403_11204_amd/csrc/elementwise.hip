@@ -32,7 +32,8 @@ __device__ __forceinline__ float wave_max(float v) {
 template <typename T>
 __global__ __launch_bounds__(256) void copy_transpose_kernel(const T* __restrict__ in, int ldin, int R, int C,
                                                              T* __restrict__ out, int ldo, T* __restrict__ outT,
-                                                             int ldt, int pad_t) {
+                                                             int ldt, int pad_t, const T* __restrict__ mask,
+                                                             int ldmask) {
   __shared__ T tile[64][65];
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -41,6 +42,8 @@ __global__ __launch_bounds__(256) void copy_transpose_kernel(const T* __restrict
     T v = from_f32<T>(0.0f);
     if (r < R && c < C) {
       v = in[(size_t)r * ldin + c];
+      // optional ReLU mask: the element passes only where mask[r][c] > 0
+      if (mask && !(to_f32(mask[(size_t)r * ldmask + c]) > 0.0f)) v = from_f32<T>(0.0f);
       if (out) out[(size_t)r * ldo + c] = v;
     }
     tile[rr][tx] = v;
@@ -251,12 +254,14 @@ __global__ void bias_update_kernel(float* __restrict__ b, float* __restrict__ vb
 }  // namespace
 
 hipError_t launch_copy_transpose(int dtype, const void* in, int ldin, int R, int C, void* out, int ldo, void* outT,
-                                 int ldt, int pad_t, hipStream_t s) {
+                                 int ldt, int pad_t, const void* mask, int ldmask, hipStream_t s) {
   dim3 grid((C + 63) / 64, (R + 63) / 64);
   if (dtype == 1)
-    copy_transpose_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)in, ldin, R, C, (bf16*)out, ldo, (bf16*)outT, ldt, pad_t);
+    copy_transpose_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)in, ldin, R, C, (bf16*)out, ldo, (bf16*)outT, ldt, pad_t,
+                                                     (const bf16*)mask, ldmask);
   else
-    copy_transpose_kernel<float><<<grid, 256, 0, s>>>((const float*)in, ldin, R, C, (float*)out, ldo, (float*)outT, ldt, pad_t);
+    copy_transpose_kernel<float><<<grid, 256, 0, s>>>((const float*)in, ldin, R, C, (float*)out, ldo, (float*)outT, ldt, pad_t,
+                                                      (const float*)mask, ldmask);
   return hipGetLastError();
 }
 

@@ -238,7 +238,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
               v[e] += bias;
               if (g.relu) v[e] = fmaxf(v[e], 0.0f);
             }
-          } else {
+          } else if (g.maskT) {   // no mask: the gradient w.r.t. the segment input
             typedef typename Vec4<T>::type mvec_t;
             const mvec_t mk = *(const mvec_t*)((const T*)g.maskT + (size_t)n * g.ldmask + mb);
 #pragma unroll
@@ -327,7 +327,11 @@ hipError_t launch_gemm(int dtype, int epi, const GemmArgs& g, hipStream_t s) {
   // the kernel addresses operands with 32-bit byte offsets and a 2 GiB sentinel
   if ((size_t)g.M * g.lda * es >= 0x80000000ull || (size_t)g.N * g.ldb * es >= 0x80000000ull) return hipErrorInvalidValue;
   if (g.lda % kLdAlign || g.ldb % kLdAlign || g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+  if (!g.A || !g.B) return hipErrorInvalidValue;                      // a missing operand must never reach the device
   if (((uintptr_t)g.A | (uintptr_t)g.B) & 15) return hipErrorInvalidValue;
+  if (epi == EPI_FWD && !g.bias) return hipErrorInvalidValue;
+  if (epi == EPI_WGRAD && !g.Cf) return hipErrorInvalidValue;
+  if (epi != EPI_WGRAD && !g.C && !g.CT) return hipErrorInvalidValue;
   const int cfg = pick_cfg(g.M, g.N);
   return dtype == 1 ? launch_epi<bf16>(epi, cfg, g, s) : launch_epi<float>(epi, cfg, g, s);
 }

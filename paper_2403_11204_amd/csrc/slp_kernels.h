@@ -40,9 +40,10 @@ hipError_t launch_gemm(int dtype, int epi, const GemmArgs& g, hipStream_t s);
 const char* gemm_config_name(int dtype, int M, int N, int K);
 
 // in[R][ldin] -> out[R][ldo] (optional) and outT[C][ldt] (optional; with pad_t the
-// columns r in [R, round_up(R,8)) of outT are zero-filled).  Element type by dtype.
+// columns r in [R, round_up(R,8)) of outT are zero-filled).  With mask (same shape as in,
+// leading dimension ldmask) an element passes only where mask > 0.  Element type by dtype.
 hipError_t launch_copy_transpose(int dtype, const void* in, int ldin, int R, int C, void* out, int ldo, void* outT,
-                                 int ldt, int pad_t, hipStream_t s);
+                                 int ldt, int pad_t, const void* mask, int ldmask, hipStream_t s);
 
 // Mean-squared-error loss against table[y[m]] and its gradient w.r.t. the
 // pre-activation (ReLU mask applied when relu_last).  Writes dZ (row-major, optional),

@@ -1,0 +1,83 @@
+"""The paper's training procedure on top of the segment step (orchestration only).
+
+Every arithmetic step below is a call into the C-ABI library; this module only
+walks the dataset in order and moves batches between segments, as the flowcharts
+of paper Sec. 2 describe:
+
+  phase 1   the left partition is trained for N_L epochs on (inputs, synthetic
+            intermediate label of the sample's class), without shuffling;
+  store     one forward pass of the trained left partition over the dataset gives
+            the stored response (read here as a separate pass after the last
+            update, so that it is deterministic);
+  phase 2   the right partition is trained for N_R epochs on (stored response, class);
+  recovery  (Sec. 5) the left partition is trained further through the frozen right
+            partition;
+  join      the partitions are chained for inference.
+
+With more than two partitions, partition k is trained on the stored response of
+partition k-1 against its own label table (Sec. 2, the multi-partition variant).
+"""
+
+import torch
+
+
+def _batches(n, batch):
+    for s in range(0, n, batch):
+        yield s, min(s + batch, n)
+
+
+def train_epochs(seg, X, y, epochs, batch):
+    """Consecutive, unshuffled batches for `epochs` passes.  Returns the mean loss of each epoch."""
+    n = X.shape[0]
+    losses = torch.zeros((epochs, (n + batch - 1) // batch), dtype=torch.float32, device=X.device)
+    for ep in range(epochs):
+        for i, (a, b) in enumerate(_batches(n, batch)):
+            losses[ep, i] = seg.step(X[a:b], y[a:b])[0]
+    return losses.mean(dim=1).tolist()
+
+
+def store_response(seg, X, batch):
+    """Forward-only pass over the dataset: the response that feeds the next partition."""
+    out = torch.empty((X.shape[0], seg.widths[-1]), dtype=X.dtype, device=X.device)
+    for a, b in _batches(X.shape[0], batch):
+        seg.forward(X[a:b], out=out[a:b])
+    return out
+
+
+def train_partitioned(segments, X, y, epochs, batch):
+    """Sequential variant: segments[k] is trained for epochs[k] on the stored response of segments[k-1].
+    Label tables must already be bound.  Returns (per-segment epoch losses, the stored responses)."""
+    losses, stored, cur = [], [], X
+    for k, seg in enumerate(segments):
+        losses.append(train_epochs(seg, cur, y, epochs[k], batch))
+        if k + 1 < len(segments):
+            cur = store_response(seg, cur, batch)
+            stored.append(cur)
+    return losses, stored
+
+
+def recovery_epochs(left, right, X, y, epochs, batch):
+    """Sec. 5: forward through left, loss and input gradient from the frozen right partition, update of left.
+    `right` must have been created with input_grad=True.  Returns the mean loss of each epoch."""
+    n = X.shape[0]
+    losses = torch.zeros((epochs, (n + batch - 1) // batch), dtype=torch.float32, device=X.device)
+    for ep in range(epochs):
+        for i, (a, b) in enumerate(_batches(n, batch)):
+            resp = left.forward(X[a:b])
+            d_resp, loss = right.input_grad(resp, y[a:b])
+            losses[ep, i] = loss[0]
+            left.step_external(X[a:b], d_resp)
+    return losses.mean(dim=1).tolist()
+
+
+def joined_forward(segments, X, batch):
+    """The joined network: logits of the last partition."""
+    cur = X
+    for seg in segments:
+        cur = store_response(seg, cur, batch)
+    return cur
+
+
+def accuracy(segments, X, y, batch):
+    logits = joined_forward(segments, X, batch)
+    return float((logits.float().argmax(dim=1) == y.long()).float().mean().item())

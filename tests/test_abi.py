@@ -30,7 +30,7 @@ def test_header_symbols_are_exported():
 def _create(widths, act=api.RELU_ALL, loss=api.MSE_SIL, dtype=api.F32, max_batch=8, lr=0.01, mom=0.9):
     L = api.lib()
     arr = (ctypes.c_int * len(widths))(*widths)
-    opts = api._Opts(dtype, max_batch, lr, mom)
+    opts = api._Opts(dtype, max_batch, lr, mom, 0)
     h = ctypes.c_void_p()
     rc = L.slp_segment_create(arr, len(widths), act, loss, ctypes.byref(opts), ctypes.byref(h))
     return rc, h
@@ -46,7 +46,7 @@ def test_create_rejects_bad_arguments():
     assert _create([4, 3], max_batch=0)[0] == -1
     assert _create([4, 3], mom=1.5)[0] == -1
     assert b"momentum" in L.slp_last_error()
-    opts = api._Opts(0, 8, 0.01, 0.9)
+    opts = api._Opts(0, 8, 0.01, 0.9, 0)
     h = ctypes.c_void_p()
     assert L.slp_segment_create(None, 2, 0, 0, ctypes.byref(opts), ctypes.byref(h)) == -1
     # 2^20 x 2^20 weights cannot be addressed
@@ -83,6 +83,8 @@ def test_sizes_and_state_errors_without_device():
     assert L.slp_segment_set_labels(h2, dummy, 47, 47) == -5
     L.slp_segment_destroy(h2)
     assert L.slp_segment_step(None, dummy, dummy, 8, None, None) == -1
+    assert L.slp_segment_input_grad(None, dummy, dummy, 8, dummy, None, None) == -1
+    assert L.slp_segment_step_external(None, dummy, dummy, 8, None) == -1
     assert L.slp_segment_param_bytes(None) == 0
 
 

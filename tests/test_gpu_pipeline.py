@@ -1,0 +1,109 @@
+"""The paper's procedure end to end on the GPU against the same procedure on the oracle:
+two-phase training with a stored response (Sec. 2), recovery epochs through the frozen
+right partition (Sec. 5), joined inference."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rng as orng
+from oracle import segment as osg
+from paper_2403_11204_amd import api, datagen, pipeline
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+TOL = {api.F32: 1e-5, api.BF16: 2e-2}
+
+
+def rel_err(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    return float(np.max(np.abs(got - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+
+
+def to_np(t):
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+def pair(widths, act, loss, dtype, max_batch, lr, mom, wseed, **kw):
+    g = api.Segment(widths, act, loss, max_batch=max_batch, dtype=dtype, lr=lr, momentum=mom, **kw)
+    o = osg.Segment(widths, act, loss, lr=lr, momentum=mom, mode="bf16" if dtype == api.BF16 else "fp32")
+    for l, (W, b) in enumerate(datagen.uniform_weights(widths, wseed)):
+        g.set_params(l, torch.from_numpy(W), torch.from_numpy(b))
+        o.set_params(l, W, b)
+    return g, o
+
+
+def dev(x, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+    return (t.to(torch.bfloat16) if dtype == api.BF16 else t).contiguous()
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+def test_recovery_step_against_oracle(dtype):
+    tol = TOL[dtype]
+    B = 90
+    gl, ol = pair([70, 130, 61], api.RELU_ALL, api.MSE_SIL, dtype, B, 0.05, 0.9, wseed=21)
+    gr, orr = pair([61, 77, 10], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, dtype, B, 0.05, 0.9, wseed=22, input_grad=True)
+    X, y = datagen.class_mean_inputs(B, 10, dim=70, seed=3)
+    Xd, yd = dev(X, dtype), torch.from_numpy(y).to(DEV)
+    Xv = to_np(Xd).astype(np.float64)
+    right_before = [gr.get_params(l)[0].clone() for l in range(2)]
+    for step in range(2):
+        resp = gl.forward(Xd)
+        d_resp, loss = gr.input_grad(resp, yd)
+        gl.step_external(Xd, d_resp)
+        o_resp = ol.forward(Xv)
+        back = orr.input_gradient(o_resp, y)
+        ol.step_external(Xv, back["dX"])
+        assert abs(float(loss.item()) - back["loss"]) <= tol * back["loss"]
+        assert rel_err(to_np(resp), o_resp) <= tol
+        # dX rows whose ReLU decisions agree are compared element-wise, all of it in the L2 sense
+        got, ref = to_np(d_resp).astype(np.float64), back["dX"]
+        assert np.linalg.norm(got - ref) <= tol * np.linalg.norm(ref)
+        if dtype == api.F32:
+            assert rel_err(got, ref) <= tol
+    for l in range(2):
+        assert rel_err(to_np(gl.get_params(l)[0]), ol.W[l]) <= tol
+        assert rel_err(to_np(gl.get_momentum(l)[0]), ol.vW[l]) <= tol
+        assert torch.equal(gr.get_params(l)[0], right_before[l])          # frozen
+    with pytest.raises(api.SlpError) as e:                                 # not created for it
+        gl.input_grad(Xd, yd)
+    assert e.value.code == -5
+
+
+def test_two_phase_training_recovery_and_join_tiny_config():
+    # tiny config, float32: 2048 blob images, batch 64; left 2 epochs on the label table, stored response,
+    # right 2 epochs on it, 1 recovery epoch, joined accuracy -- the same walk on the oracle
+    X, y = datagen.blob_images(2048, 47, 28, seed=1)
+    table = orng.make_synthetic_labels(7, 47, 64, orng.UNIFORM01, kappa=2.0)
+    gl, ol = pair([784, 128, 64], api.RELU_ALL, api.MSE_SIL, api.F32, 64, 0.05, 0.9, wseed=3)
+    gr, orr = pair([64, 64, 47], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, api.F32, 64, 0.05, 0.9, wseed=4, input_grad=True)
+    gl.set_labels(torch.from_numpy(table).to(DEV))
+    Xd, yd = torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV)
+    losses, stored = pipeline.train_partitioned([gl, gr], Xd, yd, epochs=[2, 2], batch=64)
+    rec = pipeline.recovery_epochs(gl, gr, Xd, yd, epochs=1, batch=64)
+    acc = pipeline.accuracy([gl, gr], Xd, yd, batch=64)
+
+    Xv = X.astype(np.float64)
+    ref_losses = [[], []]
+    for ep in range(2):
+        ref_losses[0].append(np.mean([ol.step(Xv[s:s + 64], y[s:s + 64], table)["loss"] for s in range(0, 2048, 64)]))
+    R = np.concatenate([ol.forward(Xv[s:s + 64]) for s in range(0, 2048, 64)])
+    for ep in range(2):
+        ref_losses[1].append(np.mean([orr.step(R[s:s + 64], y[s:s + 64])["loss"] for s in range(0, 2048, 64)]))
+    ref_rec = []
+    for s in range(0, 2048, 64):
+        back = orr.input_gradient(ol.forward(Xv[s:s + 64]), y[s:s + 64])
+        ol.step_external(Xv[s:s + 64], back["dX"])
+        ref_rec.append(back["loss"])
+    ref_logits = orr.forward(ol.forward(Xv))
+    ref_acc = float((ref_logits.argmax(axis=1) == y).mean())
+
+    # 128 float32 steps on one side, float64 on the other: the bars of a single step, widened by the walk
+    assert rel_err(to_np(stored[0]), R) <= 1e-4
+    assert np.allclose(losses[0], ref_losses[0], rtol=1e-4) and np.allclose(losses[1], ref_losses[1], rtol=1e-4)
+    assert abs(rec[0] - np.mean(ref_rec)) <= 1e-4 * np.mean(ref_rec)
+    assert losses[0][1] < losses[0][0] and losses[1][1] < losses[1][0]        # both partitions learn
+    assert abs(acc - ref_acc) <= 0.005
+    logits = to_np(pipeline.joined_forward([gl, gr], Xd, 64))
+    assert rel_err(logits, ref_logits) <= 1e-3

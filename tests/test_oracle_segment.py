@@ -355,3 +355,74 @@ def test_sampled_rows_of_a_larger_batch():
             assert np.array_equal(part["A"][l], full["A"][l][rows])
             assert np.allclose(part["dZ"][l], full["dZ"][l][rows], rtol=1e-13, atol=0)
         assert part["dW"][0] is None
+
+
+# ---------------------------------------------------------------------------------
+# recovery phase (paper Sec. 5): left partition trained through the frozen right one
+# ---------------------------------------------------------------------------------
+def _joined_loss(left, right, X, y):
+    return right.loss_and_grad(right.forward(left.forward(X)), y)[0]
+
+
+def test_recovery_gradients_by_finite_differences():
+    g = np.random.default_rng(31)
+    left = _rand_segment([6, 7, 5], osg.RELU_ALL, osg.MSE_SIL, seed=3)
+    right = _rand_segment([5, 6, 4], osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT, seed=4)
+    X = g.uniform(0, 1, (5, 6))
+    y = g.integers(0, 4, 5)
+    R = left.forward(X)
+    back = right.input_gradient(R, y)
+    assert math.isclose(back["loss"], _joined_loss(left, right, X, y), rel_tol=1e-14)
+    # dX of the right partition = d loss / d (its input), element by element
+    h = 1e-6
+    for idx in np.ndindex(R.shape):
+        Rp, Rm = R.copy(), R.copy()
+        Rp[idx] += h
+        Rm[idx] -= h
+        fd = (right.loss_and_grad(right.forward(Rp), y)[0] - right.loss_and_grad(right.forward(Rm), y)[0]) / (2 * h)
+        assert abs(fd - back["dX"][idx]) < 1e-8, idx
+    # and the left partition's parameter gradients through the frozen right partition
+    out = left.step_external(X, back["dX"], update=False)
+    for l in range(left.L):
+        for arr, grad in ((left.W[l], out["dW"][l]), (left.b[l], out["db"][l])):
+            for idx in np.ndindex(arr.shape):
+                keep = arr[idx]
+                arr[idx] = keep + h
+                lp = _joined_loss(left, right, X, y)
+                arr[idx] = keep - h
+                lm = _joined_loss(left, right, X, y)
+                arr[idx] = keep
+                assert abs((lp - lm) / (2 * h) - grad[idx]) < 1e-7, (l, idx)
+
+
+def test_recovery_steps_against_autodiff_library():
+    # joined network in an autograd library, optimiser over the LEFT parameters only
+    g = np.random.default_rng(32)
+    left = _rand_segment([8, 9, 6], osg.RELU_ALL, osg.MSE_SIL, seed=5, lr=0.05, momentum=0.9)
+    right = _rand_segment([6, 7, 5], osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT, seed=6)
+    tl = [(torch.tensor(w.copy(), requires_grad=True), torch.tensor(b.copy(), requires_grad=True)) for w, b in zip(left.W, left.b)]
+    tr = [(torch.tensor(w.copy()), torch.tensor(b.copy())) for w, b in zip(right.W, right.b)]
+    opt = torch.optim.SGD([p for wb in tl for p in wb], lr=0.05, momentum=0.9)
+    right_before = [w.copy() for w in right.W]
+    for it in range(3):
+        X = g.uniform(0, 1, (7, 8))
+        y = g.integers(0, 5, 7)
+        back = right.input_gradient(left.forward(X), y)
+        left.step_external(X, back["dX"])
+        a = torch.tensor(X)
+        for w, b in tl:
+            a = torch.relu(a @ w.T + b)                    # the cut layer keeps its ReLU
+        for i, (w, b) in enumerate(tr):
+            a = a @ w.T + b
+            if i < len(tr) - 1:
+                a = torch.relu(a)
+        lt = torch.nn.functional.cross_entropy(a, torch.tensor(y))
+        opt.zero_grad()
+        lt.backward()
+        opt.step()
+        assert math.isclose(back["loss"], lt.item(), rel_tol=1e-12)
+        for l in range(2):
+            assert np.allclose(left.W[l], tl[l][0].detach().numpy(), rtol=1e-11, atol=1e-15)
+            assert np.allclose(left.b[l], tl[l][1].detach().numpy(), rtol=1e-11, atol=1e-15)
+    for l in range(2):
+        assert np.array_equal(right.W[l], right_before[l])   # frozen
