@@ -12,10 +12,12 @@
 // no transposition on the operand path.
 //
 // gfx950 mapping
-//   * 256 threads = 4 wavefronts in a 2x2 grid; a wavefront owns a (BM/2)x(BN/2)
-//     sub-tile as MIxNI MFMA 32x32 blocks, accumulators in AGPRs (256 of them for the
-//     256x256 tile: one wavefront per SIMD, 128x128 outputs per wavefront, which is the
-//     blocking with the fewest LDS bytes per MFMA).
+//   * NW wavefronts in a 2 x NW/2 grid; a wavefront owns a (BM/2) x (BN/(NW/2)) sub-tile as
+//     MIxNI MFMA 32x32 blocks, accumulators in registers.  The 256x256 tile runs with 8
+//     wavefronts (128x64 each, 128 accumulator registers, two wavefronts per SIMD so that one
+//     can issue MFMAs while the other waits on LDS or the barrier): measured 4 % faster than
+//     4 wavefronts of 128x128 in spite of 50 % more LDS reads, and its epilogues do not spill.
+//     The 128x128 and 64x64 tiles run with 4 wavefronts.
 //   * bf16: v_mfma_f32_32x32x16_bf16, one per 16-byte chunk pair; float32:
 //     v_mfma_f32_32x32x2_f32, four per 16-byte chunk pair.  A k-tile is 128 bytes
 //     per row for both types (64 bf16 / 32 float), so loads, LDS layout and
@@ -74,16 +76,17 @@ template <typename T> struct Vec4;
 template <> struct Vec4<bf16> { typedef bf16x4 type; };
 template <> struct Vec4<float> { typedef f32x4 type; };
 
-template <typename T, int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
+template <typename T, int BM, int BN, int EPI, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // LDS-direct builtins exist in the device pass only; the host pass needs just the launch stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int ES = sizeof(T);
   constexpr int CH = Chunk<T>::elems;        // elements per 16-byte chunk
   constexpr int BK = 128 / ES;               // k elements per tile
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  constexpr int LA = BM / 32, LB = BN / 32;  // 16-byte loads per thread per k-tile
-  constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
+  constexpr int RPL = 8 * NW;                  // tile rows covered by one load instruction of the whole workgroup
+  constexpr int LA = BM / RPL, LB = BN / RPL;  // 16-byte loads per thread per k-tile
+  constexpr int WTM = BM / 2, WTN = BN / (NW / 2), MI = WTM / 32, NI = WTN / 32;
 
   // ---- workgroup -> tile ------------------------------------------------------------
   const int tilesM = (g.M + BM - 1) / BM, tilesN = (g.N + BN - 1) / BN;
@@ -118,9 +121,9 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
   const int pchunk = (lane & 7) ^ ((prow >> 1) & 7);      // logical k-chunk fetched by this lane
   uint32_t voffA[LA], voffB[LB];
 #pragma unroll
-  for (int i = 0; i < LA; ++i) voffA[i] = (uint32_t)(((size_t)(m0 + prow + 32 * i) * g.lda + pchunk * CH) * ES);
+  for (int i = 0; i < LA; ++i) voffA[i] = (uint32_t)(((size_t)(m0 + prow + RPL * i) * g.lda + pchunk * CH) * ES);
 #pragma unroll
-  for (int i = 0; i < LB; ++i) voffB[i] = (uint32_t)(((size_t)(n0 + prow + 32 * i) * g.ldb + pchunk * CH) * ES);
+  for (int i = 0; i < LB; ++i) voffB[i] = (uint32_t)(((size_t)(n0 + prow + RPL * i) * g.ldb + pchunk * CH) * ES);
   typedef __attribute__((address_space(3))) void* lds_ptr_t;
   const uint32_t lds_wave = (uint32_t)__builtin_amdgcn_readfirstlane(w * 8 * 128);
   const int kc = pchunk;
@@ -157,10 +160,10 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const GemmArgs g) {
     const bool in_k = kt * BK + kc * CH < Kr;      // past the end of K every load becomes a zero fill
     const uint32_t koff = (uint32_t)kt * 128u;
     if (i < LA)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(smem + stage * STAGE + lds_wave + i * 32 * 128), 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(smem + stage * STAGE + lds_wave + i * RPL * 128), 16,
                                                in_k ? voffA[i] + koff : kOutOfRange, 0, 0, 0);
     else
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)(smem + stage * STAGE + A_BYTES + lds_wave + (i - LA) * 32 * 128), 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)(smem + stage * STAGE + A_BYTES + lds_wave + (i - LA) * RPL * 128), 16,
                                                in_k ? voffB[i - LA] + koff : kOutOfRange, 0, 0, 0);
   };
 // s_waitcnt immediate: wait until at most n vector-memory operations are outstanding (other counters untouched)
@@ -282,27 +285,27 @@ int pick_cfg(int M, int N) {
   return 2;
 }
 
-template <typename T, int BM, int BN, int EPI>
+template <typename T, int BM, int BN, int EPI, int NW>
 hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   constexpr int smem = 2 * (BM + BN) * 128;
   static bool configured = false;   // one attribute call per instantiation
-  auto kern = gemm_nt_kernel<T, BM, BN, EPI>;
+  auto kern = gemm_nt_kernel<T, BM, BN, EPI, NW>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), smem, s, g);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * 64), smem, s, g);
   return hipGetLastError();
 }
 
 template <typename T, int EPI>
 hipError_t launch_cfg(int cfg, const GemmArgs& g, hipStream_t s) {
   switch (cfg) {
-    case 0: return launch_one<T, 256, 256, EPI>(g, s);
-    case 1: return launch_one<T, 128, 128, EPI>(g, s);
-    default: return launch_one<T, 64, 64, EPI>(g, s);
+    case 0: return launch_one<T, 256, 256, EPI, 8>(g, s);
+    case 1: return launch_one<T, 128, 128, EPI, 4>(g, s);
+    default: return launch_one<T, 64, 64, EPI, 4>(g, s);
   }
 }
 
