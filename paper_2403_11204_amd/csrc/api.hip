@@ -73,6 +73,12 @@ struct slp_segment {
   bool prof;
   std::vector<ProfRec> prof_log;
   std::vector<hipEvent_t> ev_pool;
+  // The parameter update of layer l is memory-bound and independent of the matrix products of the
+  // layers below it, so it runs on a side stream next to them (fork after the weight gradient of
+  // layer l, join at the end of the step: the caller's stream still orders everything).
+  hipStream_t side;
+  std::vector<hipEvent_t> ev_fork;   // one per layer
+  hipEvent_t ev_join;
 };
 
 namespace {
@@ -183,9 +189,20 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
     g.Cf = ly.dW; g.ldc = ly.ldk;
     int rc = run_gemm(seg, EPI_WGRAD, g, st);
     if (rc) return rc;
-    HIP_TRY(launch_bias_grad(seg->dtype, seg->dZT[l], seg->ldb, ly.N, batch, ly.db, st));
-    HIP_TRY(launch_sgd_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->lr, seg->mu, 0, st));
-    HIP_TRY(launch_bias_update(ly.b, ly.vb, ly.db, ly.N, seg->lr, seg->mu, st));
+    // fork: everything layer l still needs (bias gradient, both updates) reads dZ_l^T / dW_l, which are
+    // complete here, and writes only layer l's parameters, which nothing below reads in this step
+    hipStream_t us = l > 1 ? seg->side : st;      // the last layer has nothing left to overlap with
+    if (us != st) {
+      HIP_TRY(hipEventRecord(seg->ev_fork[l - 1], st));
+      HIP_TRY(hipStreamWaitEvent(us, seg->ev_fork[l - 1], 0));
+    }
+    HIP_TRY(launch_bias_grad(seg->dtype, seg->dZT[l], seg->ldb, ly.N, batch, ly.db, us));
+    HIP_TRY(launch_sgd_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->lr, seg->mu, 0, us));
+    HIP_TRY(launch_bias_update(ly.b, ly.vb, ly.db, ly.N, seg->lr, seg->mu, us));
+  }
+  if (seg->L > 1) {     // join: later work on the caller's stream sees every update
+    HIP_TRY(hipEventRecord(seg->ev_join, seg->side));
+    HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
   }
   return SLP_OK;
 }
@@ -325,6 +342,7 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
   s->oLoss = take(4);
   s->work_bytes = off;
 
+  s->side = nullptr; s->ev_join = nullptr;
   s->bound = false; s->have_params = false; s->table = nullptr; s->classes = 0; s->last_batch = 0; s->prof = false;
   s->partials = nullptr; s->loss_dev = nullptr;
   *out = s;
@@ -335,6 +353,9 @@ void slp_segment_destroy(slp_segment* seg) {
   if (!seg) return;
   for (auto& r : seg->prof_log) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
   for (auto e : seg->ev_pool) hipEventDestroy(e);
+  for (auto e : seg->ev_fork) hipEventDestroy(e);
+  if (seg->ev_join) hipEventDestroy(seg->ev_join);
+  if (seg->side) hipStreamDestroy(seg->side);
   delete seg;
 }
 
@@ -369,6 +390,15 @@ int slp_segment_bind(slp_segment* seg, void* params, size_t params_bytes, void* 
   }
   seg->partials = (float*)at(seg->oPartials);
   seg->loss_dev = (float*)at(seg->oLoss);
+  if (!seg->side) {     // host-side objects only; default priority
+    HIP_TRY(hipStreamCreateWithFlags(&seg->side, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&seg->ev_join, hipEventDisableTiming));
+    for (int l = 0; l < seg->L; ++l) {
+      hipEvent_t e = nullptr;
+      HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      seg->ev_fork.push_back(e);
+    }
+  }
   seg->bound = true;
   seg->have_params = false;
   return SLP_OK;
