@@ -222,6 +222,10 @@ def main():
     }
     if not cfg["streams"]:
         out["per_segment_gemm_ms"] = [p[0] / steps for p in prof]
+    # what the matrix pipe sustains on this chip with no memory traffic at all (register-only MFMA loop, ~50 ms)
+    sustained, _ = api.probe_mfma_rate(dt, iters=20000 if dt == api.BF16 else 4000)
+    out["roofline"]["sustained_mfma_only"] = sustained
+    out["roofline"]["frac_of_sustained"] = achieved / sustained
 
     if args.config == 4 and not args.no_e2e:
         # conventional end-to-end backprop through all six layers on the same GPU, same library

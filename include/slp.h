@@ -171,6 +171,20 @@ int slp_segment_step_external(slp_segment* seg, const void* X /*device*/, const 
 int slp_segment_profile_enable(slp_segment* seg, int on);
 int slp_segment_profile_read(slp_segment* seg, double* gemm_ms, int64_t* gemm_launches, double* gemm_flops);
 
+/* Sustained matrix-pipe rate of the device the caller has made current: a register-only
+ * loop of the MFMA instructions the matrix products use (bf16 32x32x16 or float32
+ * 32x32x2, 8 wavefronts per compute unit, one workgroup per compute unit, pseudo-random
+ * operands), `iters` iterations of 16 MFMA groups per wavefront, timed with HIP events
+ * on `stream` after a short warm-up launch.  Synchronous.  It is the rate the chip holds
+ * under its power limit with no memory traffic at all: the practical ceiling to read a
+ * measured matrix-product rate against, beside the published peak.
+ * scratch: device buffer of at least 2048 bytes per compute unit (caller-owned, overwritten).
+ * tflops_out (host) receives the rate in TFLOP/s, ms_out (host, may be NULL) the duration.
+ * Errors: SLP_ERR_ARG (dtype, iters outside [1, 2^24], null pointers), SLP_ERR_SHAPE
+ * (scratch too small), SLP_ERR_DEVICE. */
+int slp_probe_mfma_rate(int dtype, int iters, void* scratch /*device*/, size_t scratch_bytes, double* tflops_out /*host*/,
+                        double* ms_out /*host, may be NULL*/, slp_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

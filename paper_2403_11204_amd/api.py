@@ -64,6 +64,7 @@ def lib():
         "slp_segment_step_external": (i32, [vp, vp, vp, i32, vp]),
         "slp_segment_profile_enable": (i32, [vp, i32]),
         "slp_segment_profile_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]),
+        "slp_probe_mfma_rate": (i32, [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -77,7 +78,7 @@ EXPORTS = ["slp_last_error", "slp_make_synthetic_labels", "slp_make_segment_inpu
            "slp_segment_init", "slp_segment_set_params", "slp_segment_get_params", "slp_segment_get_grads",
            "slp_segment_get_momentum", "slp_segment_get_activation", "slp_segment_set_lr", "slp_segment_set_labels",
            "slp_segment_step", "slp_segment_forward", "slp_segment_input_grad", "slp_segment_step_external",
-           "slp_segment_profile_enable", "slp_segment_profile_read"]
+           "slp_segment_profile_enable", "slp_segment_profile_read", "slp_probe_mfma_rate"]
 
 
 def _check(code):
@@ -111,6 +112,14 @@ def make_segment_inputs(seed, table, y, first_sample, sigma, dtype=F32):
     _check(lib().slp_make_segment_inputs(seed, _ptr(table), table.shape[0], _ptr(y), first_sample, y.numel(),
                                          table.shape[1], sigma, _ptr(out), dtype, _stream()))
     return out
+
+
+def probe_mfma_rate(dtype=BF16, iters=20000, device="cuda"):
+    """slp_probe_mfma_rate: (TFLOP/s, ms) of the register-only MFMA loop on the current device."""
+    scratch = torch.empty(1 << 20, dtype=torch.float32, device=device)      # 4 MiB >= 2048 B per compute unit
+    tf, ms = ctypes.c_double(), ctypes.c_double()
+    _check(lib().slp_probe_mfma_rate(dtype, iters, _ptr(scratch), scratch.numel() * 4, ctypes.byref(tf), ctypes.byref(ms), _stream()))
+    return tf.value, ms.value
 
 
 class Segment:

@@ -31,6 +31,7 @@ UNITS = {
     "rng.hip": ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"],
     "elementwise.hip": [],
     "gemm.hip": [],
+    "probe.hip": [],
 }
 
 

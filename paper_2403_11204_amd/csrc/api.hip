@@ -588,4 +588,35 @@ int slp_segment_profile_read(slp_segment* seg, double* gemm_ms, int64_t* gemm_la
   return SLP_OK;
 }
 
+int slp_probe_mfma_rate(int dtype, int iters, void* scratch, size_t scratch_bytes, double* tflops, double* ms, slp_stream stream) {
+  if (dtype != SLP_F32 && dtype != SLP_BF16) return fail(SLP_ERR_ARG, "slp_probe_mfma_rate: unknown dtype %d", dtype);
+  if (iters <= 0 || iters > (1 << 24)) return fail(SLP_ERR_ARG, "slp_probe_mfma_rate: iters %d outside [1, 2^24]", iters);
+  if (!scratch || !tflops) return fail(SLP_ERR_ARG, "slp_probe_mfma_rate: null scratch or result pointer");
+  int dev = 0, cus = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const size_t per_wg = 512 * sizeof(float);
+  if (scratch_bytes < per_wg * (size_t)cus)
+    return fail(SLP_ERR_SHAPE, "slp_probe_mfma_rate: scratch of %zu bytes, %zu needed (%d compute units x 2048)", scratch_bytes,
+                per_wg * (size_t)cus, cus);
+  hipStream_t s = (hipStream_t)stream;
+  hipEvent_t a = nullptr, b = nullptr;
+  HIP_TRY(hipEventCreate(&a));
+  HIP_TRY(hipEventCreate(&b));
+  double fl = 0.0;
+  hipError_t e = launch_mfma_probe(dtype, iters / 8 + 1, cus, (float*)scratch, &fl, s);   // warm-up: clocks settle
+  if (e == hipSuccess) e = hipEventRecord(a, s);
+  if (e == hipSuccess) e = launch_mfma_probe(dtype, iters, cus, (float*)scratch, &fl, s);
+  if (e == hipSuccess) e = hipEventRecord(b, s);
+  if (e == hipSuccess) e = hipEventSynchronize(b);
+  float t = 0.0f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&t, a, b);
+  hipEventDestroy(a);
+  hipEventDestroy(b);
+  if (e != hipSuccess) return fail(SLP_ERR_DEVICE, "slp_probe_mfma_rate: %s", hipGetErrorString(e));
+  *tflops = fl * cus * iters / (t * 1e-3) / 1e12;
+  if (ms) *ms = t;
+  return SLP_OK;
+}
+
 }  // extern "C"

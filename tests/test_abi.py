@@ -97,3 +97,8 @@ def test_free_functions_reject_bad_arguments():
     assert L.slp_make_synthetic_labels(1, 4, 8, 0, 1.0, dummy, 3, None) == -1
     assert L.slp_make_segment_inputs(1, None, 4, dummy, 0, 2, 8, 0.05, dummy, 0, None) == -1
     assert L.slp_make_segment_inputs(1, dummy, 4, dummy, -1, 2, 8, 0.05, dummy, 0, None) == -1
+    tf = ctypes.c_double()
+    assert L.slp_probe_mfma_rate(7, 10, dummy, 1 << 22, ctypes.byref(tf), None, None) == -1
+    assert L.slp_probe_mfma_rate(1, 0, dummy, 1 << 22, ctypes.byref(tf), None, None) == -1
+    assert L.slp_probe_mfma_rate(1, 10, None, 1 << 22, ctypes.byref(tf), None, None) == -1
+    assert L.slp_probe_mfma_rate(1, 10, dummy, 1 << 22, None, None, None) == -1

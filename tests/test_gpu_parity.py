@@ -5,6 +5,8 @@ Tolerances (per tensor, max|gpu - ref| / max|ref|):
   bf16 path     2e-2   (bf16 storage, float32 accumulation)
 Labels, generated inputs, initial weights and gather indices are bit-exact."""
 
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -278,3 +280,14 @@ def test_step_argument_errors():
     with pytest.raises(api.SlpError) as e:
         fresh.step(X[:8], y[:8])              # no parameters yet
     assert e.value.code == -5
+
+
+def test_mfma_probe_reports_a_rate_below_the_published_peak():
+    for dtype, peak in ((api.BF16, 2516.6), (api.F32, 157.3)):
+        tf, ms = api.probe_mfma_rate(dtype, iters=2000)
+        assert ms > 0 and 0.05 * peak < tf < 1.02 * peak, (dtype, tf, ms)
+    with pytest.raises(api.SlpError) as e:
+        tf = ctypes.c_double()
+        small = torch.empty(16, device=DEV)
+        api._check(api.lib().slp_probe_mfma_rate(api.BF16, 10, api._ptr(small), 64, ctypes.byref(tf), None, None))
+    assert e.value.code == -2
