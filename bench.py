@@ -42,13 +42,13 @@ ALL, LAST = api.RELU_ALL, api.RELU_HIDDEN_IDENTITY_LAST
 
 # name, dtype, batch, classes, samples, optimiser, segments: (widths, act, loss, label dist, label seed)
 CONFIGS = {
-    0: dict(name="tiny 784-128-64 | 64-64-47 fp32", dtype=api.F32, batch=64, classes=47, lr=0.01, mom=0.0, streams=False,
+    0: dict(name="tiny 784-128-64 | 64-64-47 fp32", dtype=api.F32, batch=64, classes=47, lr=0.01, mom=0.0, streams=False, graph=True,
             segs=[([784, 128, 64], ALL, MSE, api.UNIFORM_PM1, 7), ([64, 64, 47], LAST, CE, None, None)]),
     1: dict(name="paper-shaped 784-1024-1024-512 | 512-1024-1024-47 fp32", dtype=api.F32, batch=256, classes=47, lr=0.01,
-            mom=0.9, streams=False,
+            mom=0.9, streams=False, graph=True,
             segs=[([784, 1024, 1024, 512], ALL, MSE, api.NORMAL, 11), ([512, 1024, 1024, 47], LAST, CE, None, None)]),
     2: dict(name="wide 784-4096-4096-2048 | 2048-4096-4096-47 bf16", dtype=api.BF16, batch=1024, classes=47, lr=0.01,
-            mom=0.9, streams=False,
+            mom=0.9, streams=False, graph=True,
             segs=[([784, 4096, 4096, 2048], ALL, MSE, api.BINARY_PM1, 13), ([2048, 4096, 4096, 47], LAST, CE, None, None)]),
     3: dict(name="deep 12x8192 in 4 segments on 4 streams bf16", dtype=api.BF16, batch=4096, classes=100, lr=0.01, mom=0.9,
             streams=True,
@@ -81,6 +81,8 @@ def build_segments(cfg, n_batches):
     for si, (widths, act, loss, dist, seed) in enumerate(cfg["segs"]):
         seg = api.Segment(widths, act, loss, max_batch=B, dtype=dt, lr=cfg["lr"], momentum=cfg["mom"])
         seg.init(100 + si)
+        if cfg.get("graph"):        # launch-bound sizes: replay the captured launch sequence of a step
+            seg.set_graph(True)
         if si == 0:
             inputs.append(X0)
         else:   # an interior/final segment sees the previous cut's label of the class plus noise (sigma 0.05)
@@ -175,12 +177,16 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=None)
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run one plain 1 GiB -> 1 GiB elementwise copy kernel (scale reference for HBM byte counters)")
+    ap.add_argument("--eager", action="store_true", help="configs 0-2: launch every kernel of a step instead of replaying graphs")
+    ap.add_argument("--serial", action="store_true", help="config 3: run the four segments one after another on one stream")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (segments are independent jobs; no collectives exist): use --gpus 1")
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
-    cfg = CONFIGS[args.config]
+    cfg = dict(CONFIGS[args.config])
+    if args.serial:
+        cfg["streams"] = False
     big = args.config >= 3
     steps = args.steps if args.steps is not None else (20 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
@@ -196,7 +202,16 @@ def main():
     torch.cuda.reset_peak_memory_stats()
     segs, inputs, ys = build_segments(cfg, n_batches=2 if big else 8)
     torch.cuda.synchronize()
-    wall_ms, ev_ms, prof = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup)
+    if cfg.get("graph") and not args.eager:
+        # graphs cannot be captured on the null stream; the matrix products are timed in a second, eager pass
+        # (launch-by-launch events and replayed graphs exclude each other)
+        with torch.cuda.stream(torch.cuda.Stream()):
+            wall_ms, ev_ms, _ = time_workload(segs, inputs, ys, False, steps, warmup, profile=False)
+            prof_steps = max(steps // 4, 10)
+            _, _, prof = time_workload(segs, inputs, ys, False, prof_steps, 2)
+    else:
+        prof_steps = steps
+        wall_ms, ev_ms, prof = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup)
     ms = max(wall_ms, ev_ms) if not cfg["streams"] else wall_ms
     flops_step = sum(gemm_flops_per_sample(s[0]) for s in cfg["segs"]) * B
     peak = PEAK_TFLOPS[dt]
@@ -211,7 +226,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if dt == api.BF16 else "f32", "data": "synthetic",
         "config": {"workload": cfg["name"], "global_batch": B, "classes": cfg["classes"],
                    "segments": [s[0] for s in cfg["segs"]], "optimizer": "sgd lr %g momentum %g" % (cfg["lr"], cfg["mom"]),
-                   "concurrent_streams": len(segs) if cfg["streams"] else 1},
+                   "concurrent_streams": len(segs) if cfg["streams"] else 1,
+                   "launch": "hip graph replay" if cfg.get("graph") and not args.eager else "eager"},
         "step_tflops": flops_step / (ms * 1e-3) / 1e12,
         "step_frac_of_mfma_peak": flops_step / (ms * 1e-3) / 1e12 / peak,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
@@ -221,7 +237,7 @@ def main():
         "peak_hbm_bytes_torch": int(torch.cuda.max_memory_allocated()),
     }
     if not cfg["streams"]:
-        out["per_segment_gemm_ms"] = [p[0] / steps for p in prof]
+        out["per_segment_gemm_ms"] = [p[0] / prof_steps for p in prof]
     # what the matrix pipe sustains on this chip with no memory traffic at all (register-only MFMA loop, ~50 ms)
     sustained, _ = api.probe_mfma_rate(dt, iters=20000 if dt == api.BF16 else 4000)
     out["roofline"]["sustained_mfma_only"] = sustained

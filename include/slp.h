@@ -161,6 +161,21 @@ int slp_segment_input_grad(slp_segment* seg, const void* X /*device*/, const int
 int slp_segment_step_external(slp_segment* seg, const void* X /*device*/, const void* dA_out /*device*/, int batch,
                               slp_stream stream);
 
+/* ---- launch-bound segments ----------------------------------------------------------
+ * A step of a small segment (the paper's own network is 784-80-60 | 60-60-47, Sec. 3) is a
+ * few dozen kernels of a few microseconds each: the host's launch rate, not the GPU, bounds
+ * it.  With graphs on, slp_segment_step captures its launch sequence into a HIP graph the
+ * first time it sees a combination (X, targets, batch, loss_out) -- the only arguments the
+ * sequence depends on -- and replays that graph, one launch, on every later call with the
+ * same combination (up to 16 are kept, least recently used evicted).  Results are those of
+ * the eager launches, bit for bit: the same kernels with the same arguments in the same order.
+ * Eager launches are used regardless while launches are being timed (profile hooks on), on the
+ * null stream, for the first step of a handle, and when `stream` is already being captured by
+ * the caller (the launches then become part of the caller's graph).  slp_segment_set_lr,
+ * slp_segment_set_labels and slp_segment_bind drop the captured graphs (after a device
+ * synchronisation), because those hold their values.  Off by default. */
+int slp_segment_set_graph(slp_segment* seg, int on);
+
 /* ---- measurement hooks -------------------------------------------------------------
  * When enabled, every matrix-product launch of the segment is bracketed by HIP
  * events on its stream.  slp_segment_profile_read synchronises the recorded events,

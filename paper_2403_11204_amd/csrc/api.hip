@@ -51,6 +51,18 @@ struct Layer {
 
 struct ProfRec { hipEvent_t a, b; double flops; };
 
+// One captured training step: the launch sequence depends on these arguments only
+// (every other kernel argument is fixed once the handle is bound).
+struct StepGraph {
+  const void* X;
+  const int32_t* targets;
+  int batch;
+  float* loss_out;
+  hipGraphExec_t exec;
+  uint64_t used;
+};
+constexpr size_t kMaxStepGraphs = 16;
+
 }  // namespace
 
 struct slp_segment {
@@ -79,11 +91,23 @@ struct slp_segment {
   hipStream_t side;
   std::vector<hipEvent_t> ev_fork;   // one per layer
   hipEvent_t ev_join;
+  // Small segments are bound by launch latency, not by the GPU: with graphs on, the launch sequence of a step
+  // is captured once per (X, targets, batch, loss_out) and replayed as one graph launch afterwards.
+  bool use_graph, graph_warm;
+  std::vector<StepGraph> graphs;
+  uint64_t graph_tick;
 };
 
 namespace {
 
 int esize(const slp_segment* s) { return s->dtype == SLP_BF16 ? 2 : 4; }
+
+// captured steps hold lr, momentum, the label table and the buffer addresses by value
+void drop_graphs(slp_segment* s) {
+  if (!s->graphs.empty()) (void)hipDeviceSynchronize();   // a replay may still be running; rare (set-up calls only)
+  for (auto& g : s->graphs) hipGraphExecDestroy(g.exec);
+  s->graphs.clear();
+}
 bool relu_on(const slp_segment* s, int l) { return l < s->L || s->act == SLP_RELU_ALL; }
 
 hipEvent_t get_event(slp_segment* s) {
@@ -344,6 +368,7 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
 
   s->side = nullptr; s->ev_join = nullptr;
   s->bound = false; s->have_params = false; s->table = nullptr; s->classes = 0; s->last_batch = 0; s->prof = false;
+  s->use_graph = false; s->graph_warm = false; s->graph_tick = 0;
   s->partials = nullptr; s->loss_dev = nullptr;
   *out = s;
   return SLP_OK;
@@ -355,6 +380,7 @@ void slp_segment_destroy(slp_segment* seg) {
   for (auto e : seg->ev_pool) hipEventDestroy(e);
   for (auto e : seg->ev_fork) hipEventDestroy(e);
   if (seg->ev_join) hipEventDestroy(seg->ev_join);
+  drop_graphs(seg);
   if (seg->side) hipStreamDestroy(seg->side);
   delete seg;
 }
@@ -371,6 +397,8 @@ int slp_segment_bind(slp_segment* seg, void* params, size_t params_bytes, void* 
   if (params_bytes < seg->param_bytes) return fail(SLP_ERR_ALLOC, "params buffer has %zu bytes, %zu needed", params_bytes, seg->param_bytes);
   if (workspace_bytes < seg->work_bytes) return fail(SLP_ERR_ALLOC, "workspace has %zu bytes, %zu needed", workspace_bytes, seg->work_bytes);
   hipStream_t st = (hipStream_t)stream;
+  drop_graphs(seg);      // captured steps hold the old buffers' addresses
+  seg->graph_warm = false;
   HIP_TRY(hipMemsetAsync(params, 0, seg->param_bytes, st));
   HIP_TRY(hipMemsetAsync(workspace, 0, seg->work_bytes, st));
   char* p = (char*)params;
@@ -461,6 +489,7 @@ int slp_segment_set_lr(slp_segment* seg, float lr, float momentum) {
   if (rc) return rc;
   if (!(lr >= 0.0f) || !(momentum >= 0.0f && momentum < 1.0f)) return fail(SLP_ERR_ARG, "lr must be >= 0 and momentum in [0,1)");
   seg->lr = lr; seg->mu = momentum;
+  drop_graphs(seg);
   return SLP_OK;
 }
 
@@ -471,6 +500,7 @@ int slp_segment_set_labels(slp_segment* seg, const float* table, int classes, in
   if (!table || classes <= 0) return fail(SLP_ERR_ARG, "table must not be NULL and classes positive");
   if (dim != seg->widths[seg->L]) return fail(SLP_ERR_SHAPE, "label dim %d != last width %d", dim, seg->widths[seg->L]);
   seg->table = table; seg->classes = classes;
+  drop_graphs(seg);
   return SLP_OK;
 }
 
@@ -497,16 +527,64 @@ int slp_segment_step(slp_segment* seg, const void* X, const int32_t* targets, in
   if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
   if (seg->loss == SLP_MSE_SIL && !seg->table) return fail(SLP_ERR_STATE, "no label table bound: call slp_segment_set_labels first");
   hipStream_t st = (hipStream_t)stream;
-
-  rc = ingest(seg, X, batch, true, st);
-  if (rc) return rc;
-  rc = forward_layers(seg, batch, true, st);
-  if (rc) return rc;
-  rc = loss_and_output_grad(seg, targets, batch, loss_out, st);
-  if (rc) return rc;
-  rc = backward_and_update(seg, batch, st);
-  if (rc) return rc;
   seg->last_batch = batch;
+
+  auto launch_all = [&]() -> int {
+    int r = ingest(seg, X, batch, true, st);
+    if (!r) r = forward_layers(seg, batch, true, st);
+    if (!r) r = loss_and_output_grad(seg, targets, batch, loss_out, st);
+    if (!r) r = backward_and_update(seg, batch, st);
+    return r;
+  };
+  // Eager launches when graphs are off, when launches are being timed one by one, on the null stream (it
+  // cannot be captured), and when the caller is capturing this stream already (the launches then go into
+  // the caller's graph).  The first step of a handle is eager too, so that one-time kernel set-up is over
+  // before anything is captured.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (seg->use_graph && st) HIP_TRY(hipStreamIsCapturing(st, &cap));
+  if (!seg->use_graph || seg->prof || !st || cap != hipStreamCaptureStatusNone || !seg->graph_warm) {
+    seg->graph_warm = true;
+    return launch_all();
+  }
+  ++seg->graph_tick;
+  for (auto& g : seg->graphs)
+    if (g.X == X && g.targets == targets && g.batch == batch && g.loss_out == loss_out) {
+      g.used = seg->graph_tick;
+      HIP_TRY(hipGraphLaunch(g.exec, st));
+      return SLP_OK;
+    }
+  HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+  rc = launch_all();
+  hipGraph_t graph = nullptr;
+  hipError_t e = hipStreamEndCapture(st, &graph);      // always ended, so that the stream is usable after an error
+  if (rc || e != hipSuccess) {
+    if (graph) hipGraphDestroy(graph);
+    return rc ? rc : fail(SLP_ERR_DEVICE, "hipStreamEndCapture: %s", hipGetErrorString(e));
+  }
+  StepGraph sg{X, targets, batch, loss_out, nullptr, seg->graph_tick};
+  e = hipGraphInstantiate(&sg.exec, graph, nullptr, nullptr, 0);
+  hipGraphDestroy(graph);
+  if (e != hipSuccess) return fail(SLP_ERR_DEVICE, "hipGraphInstantiate: %s", hipGetErrorString(e));
+  if (seg->graphs.size() >= kMaxStepGraphs) {          // evict the least recently used
+    size_t v = 0;
+    for (size_t i = 1; i < seg->graphs.size(); ++i)
+      if (seg->graphs[i].used < seg->graphs[v].used) v = i;
+    HIP_TRY(hipDeviceSynchronize());                   // its last replay may still be running
+    hipGraphExecDestroy(seg->graphs[v].exec);
+    seg->graphs[v] = sg;
+  } else {
+    seg->graphs.push_back(sg);
+  }
+  HIP_TRY(hipGraphLaunch(sg.exec, st));
+  return SLP_OK;
+}
+
+int slp_segment_set_graph(slp_segment* seg, int on) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  if (on) HIP_TRY(gemm_configure_all());
+  seg->use_graph = on != 0;
+  if (!seg->use_graph) drop_graphs(seg);
   return SLP_OK;
 }
 

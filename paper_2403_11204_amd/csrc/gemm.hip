@@ -113,11 +113,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.A), 0, (int)((size_t)g.M * g.lda * ES), 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcB =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.B), 0, (int)((size_t)g.N * g.ldb * ES), 0x00020000);
-  // Direct-to-LDS loads: load i of wavefront w fills LDS rows [8w + 32i, 8w + 32i + 8) of the tile,
-  // lane l writing 16 bytes at (row 8w + 32i + l/8, physical chunk l%8) -- the hardware places lane l
-  // at base + 16*l.  The XOR swizzle is therefore applied on the global side: the lane fetches the
-  // logical chunk that belongs at its physical position.
-  const int prow = w * 8 + (lane >> 3);                   // + 32 i
+  // Direct-to-LDS loads: load i of wavefront w fills LDS rows [8w + RPL i, 8w + RPL i + 8) of the tile
+  // (RPL = 8 x wavefronts), lane l writing 16 bytes at (row 8w + RPL i + l/8, physical chunk l%8) --
+  // the hardware places lane l at base + 16*l.  The XOR swizzle is therefore applied on the global
+  // side: the lane fetches the logical chunk that belongs at its physical position.
+  const int prow = w * 8 + (lane >> 3);                   // + RPL i
   const int pchunk = (lane & 7) ^ ((prow >> 1) & 7);      // logical k-chunk fetched by this lane
   uint32_t voffA[LA], voffB[LB];
 #pragma unroll
@@ -286,15 +286,23 @@ int pick_cfg(int M, int N) {
 }
 
 template <typename T, int BM, int BN, int EPI, int NW>
-hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
+hipError_t configure_one() {
   constexpr int smem = 2 * (BM + BN) * 128;
   static bool configured = false;   // one attribute call per instantiation
-  auto kern = gemm_nt_kernel<T, BM, BN, EPI, NW>;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_nt_kernel<T, BM, BN, EPI, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     configured = true;
   }
+  return hipSuccess;
+}
+
+template <typename T, int BM, int BN, int EPI, int NW>
+hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
+  constexpr int smem = 2 * (BM + BN) * 128;
+  auto kern = gemm_nt_kernel<T, BM, BN, EPI, NW>;
+  hipError_t e = configure_one<T, BM, BN, EPI, NW>();
+  if (e != hipSuccess) return e;
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * 64), smem, s, g);
   return hipGetLastError();
@@ -318,7 +326,27 @@ hipError_t launch_epi(int epi, int cfg, const GemmArgs& g, hipStream_t s) {
   }
 }
 
+template <typename T, int EPI>
+hipError_t configure_epi() {
+  hipError_t e = configure_one<T, 256, 256, EPI, 8>();
+  if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 4>();
+  if (e == hipSuccess) e = configure_one<T, 64, 64, EPI, 4>();
+  return e;
+}
+
 }  // namespace
+
+// One-time kernel attributes of every instantiation, so that no launch has to set one later
+// (a launch sequence that is being captured into a graph should consist of launches only).
+hipError_t gemm_configure_all() {
+  hipError_t e = configure_epi<bf16, EPI_FWD>();
+  if (e == hipSuccess) e = configure_epi<bf16, EPI_DGRAD>();
+  if (e == hipSuccess) e = configure_epi<bf16, EPI_WGRAD>();
+  if (e == hipSuccess) e = configure_epi<float, EPI_FWD>();
+  if (e == hipSuccess) e = configure_epi<float, EPI_DGRAD>();
+  if (e == hipSuccess) e = configure_epi<float, EPI_WGRAD>();
+  return e;
+}
 
 const char* gemm_config_name(int dtype, int M, int N, int K) {
   (void)dtype; (void)K;

@@ -77,6 +77,9 @@ hipError_t launch_make_inputs(uint64_t seed, const float* table, int classes, co
                               int batch, int dim, float sigma, void* out, int dt, hipStream_t s);
 hipError_t launch_init_weights(uint64_t seed, int layer, float* W32, int N, int K, int ldk, float* b, hipStream_t s);
 
+// Sets the one-time attributes of every matrix-product kernel instantiation (needs a current device).
+hipError_t gemm_configure_all();
+
 // Register-only MFMA loop (no memory traffic) on `grid` workgroups of 512 threads; sink holds grid*512 floats.
 hipError_t launch_mfma_probe(int dtype, int iters, int grid, float* sink, double* flops_per_workgroup_iter, hipStream_t s);
 
