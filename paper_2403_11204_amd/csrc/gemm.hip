@@ -76,6 +76,48 @@ template <typename T> struct Vec4;
 template <> struct Vec4<bf16> { typedef bf16x4 type; };
 template <> struct Vec4<float> { typedef f32x4 type; };
 
+// Epilogue of four consecutive rows mb..mb+3 of output column n (one accumulator register quad).
+//   EPI_FWD  : + bias, optional ReLU;  EPI_DGRAD: zero where the mask (stored transposed) is not positive;
+//   both store row-major C and/or transposed CT in T (the transposed store is one vector; rows past M up to
+//   the next multiple of 8 are written as zero there);  EPI_WGRAD: float32 row-major.
+template <typename T, int EPI>
+__device__ __forceinline__ void store_quad(const GemmArgs& g, int n, int mb, float bias, float (&v)[4]) {
+  if (EPI == EPI_WGRAD) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (mb + e < g.M) g.Cf[(size_t)(mb + e) * g.ldc + n] = v[e];
+    return;
+  }
+  if (mb >= ((g.M + 7) & ~7)) return;
+  if (EPI == EPI_FWD) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[e] += bias;
+      if (g.relu) v[e] = fmaxf(v[e], 0.0f);
+    }
+  } else if (g.maskT) {   // no mask: the gradient w.r.t. the segment input
+    typedef typename Vec4<T>::type mvec_t;
+    const mvec_t mk = *(const mvec_t*)((const T*)g.maskT + (size_t)n * g.ldmask + mb);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (!((float)mk[e] > 0.0f)) v[e] = 0.0f;
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (mb + e >= g.M) v[e] = 0.0f;
+  if (g.C) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (mb + e < g.M) ((T*)g.C)[(size_t)(mb + e) * g.ldc + n] = (T)v[e];
+  }
+  if (g.CT) {
+    typename Vec4<T>::type o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (T)v[e];
+    *(typename Vec4<T>::type*)((T*)g.CT + (size_t)n * g.ldct + mb) = o;
+  }
+}
+
 template <typename T, int BM, int BN, int EPI, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // LDS-direct builtins exist in the device pass only; the host pass needs just the launch stub
@@ -214,7 +256,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
   // Accumulator layout of the 32x32 MFMA: lane holds column n = lane & 31 and, in
   // register r, row 8*(r/4) + 4*(lane/32) + (r%4): four consecutive rows per register
   // quad, which is what makes the transposed store a vector store.
-  const int M8 = (g.M + 7) & ~7;
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int n = n0 + wn * WTN + j * 32 + l32;
@@ -225,49 +266,110 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int mb = m0 + wm * WTM + i * 32 + 8 * q + 4 * half;   // rows mb .. mb+3
-        if (EPI == EPI_WGRAD) {
+        float v[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (mb + e < g.M) g.Cf[(size_t)(mb + e) * g.ldc + n] = acc[i][j][4 * q + e];
-        } else {
-          if (mb >= M8) continue;
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-          if (EPI == EPI_FWD) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              v[e] += bias;
-              if (g.relu) v[e] = fmaxf(v[e], 0.0f);
-            }
-          } else if (g.maskT) {   // no mask: the gradient w.r.t. the segment input
-            typedef typename Vec4<T>::type mvec_t;
-            const mvec_t mk = *(const mvec_t*)((const T*)g.maskT + (size_t)n * g.ldmask + mb);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (!((float)mk[e] > 0.0f)) v[e] = 0.0f;
-          }
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (mb + e >= g.M) v[e] = 0.0f;
-          if (g.C) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (mb + e < g.M) ((T*)g.C)[(size_t)(mb + e) * g.ldc + n] = (T)v[e];
-          }
-          if (g.CT) {
-            typename Vec4<T>::type o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (T)v[e];
-            *(typename Vec4<T>::type*)((T*)g.CT + (size_t)n * g.ldct + mb) = o;
-          }
-        }
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+        store_quad<T, EPI>(g, n, m0 + wm * WTM + i * 32 + 8 * q + 4 * half, bias, v);
         // keep the scheduler from hoisting every block's address arithmetic and mask
         // loads to the top of the epilogue (that spills registers)
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+  }
+#endif
+}
+
+// Small products: a grid of 64x64 tiles that covers less than half of the compute units leaves
+// most matrix pipes idle, and one wavefront cannot drive more than its own SIMD's pipe.  This
+// variant cuts the output into 32x32 tiles (4x as many workgroups) and splits the CONTRACTION over
+// the 4 wavefronts of a workgroup instead: every k-tile of 128 bytes per row is 4 chunk pairs,
+// wavefront w multiplies pair w of every k-tile into its own 32x32 accumulator, and the four
+// partial accumulators are added through LDS in a fixed order (0,1,2,3: deterministic) before the
+// shared epilogue.  Same LDS-direct loads, row layout and swizzle as the kernel above; four
+// stages of 8 KB, loads three k-tiles ahead, one barrier per k-tile.
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void gemm_nt_ksplit_kernel(const GemmArgs g) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // 4 stages of 64 rows x 128 bytes
+  constexpr int ES = sizeof(T);
+  constexpr int CH = Chunk<T>::elems;
+  constexpr int BK = 128 / ES;
+  constexpr int STAGE = 64 * 128, NS = 4;
+
+  const int tilesM = (g.M + 31) / 32;
+  const int tm = blockIdx.x % tilesM, tn = blockIdx.x / tilesM;   // neighbours share the B rows
+  const int m0 = tm * 32, n0 = tn * 32;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+
+  const int Kr = (g.K + CH - 1) / CH * CH;
+  const __amdgpu_buffer_rsrc_t rsrcA =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.A), 0, (int)((size_t)g.M * g.lda * ES), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.B), 0, (int)((size_t)g.N * g.ldb * ES), 0x00020000);
+  // one load instruction of the workgroup covers 32 rows: wavefront w rows [8w, 8w+8), lane l -> (row 8w + l/8, chunk l%8)
+  const int prow = w * 8 + (lane >> 3);
+  const int pchunk = (lane & 7) ^ ((prow >> 1) & 7);
+  const uint32_t voffA = (uint32_t)(((size_t)(m0 + prow) * g.lda + pchunk * CH) * ES);
+  const uint32_t voffB = (uint32_t)(((size_t)(n0 + prow) * g.ldb + pchunk * CH) * ES);
+  typedef __attribute__((address_space(3))) void* lds_ptr_t;
+  const uint32_t lds_wave = (uint32_t)__builtin_amdgcn_readfirstlane(w * 8 * 128);
+  auto gload = [&](int kt) {
+    const bool in_k = kt * BK + pchunk * CH < Kr;      // past the end of K every load becomes a zero fill
+    const uint32_t koff = (uint32_t)kt * 128u;
+    unsigned char* sb = smem + (kt & (NS - 1)) * STAGE + lds_wave;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)sb, 16, in_k ? voffA + koff : kOutOfRange, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)(sb + 32 * 128), 16, in_k ? voffB + koff : kOutOfRange, 0, 0, 0);
+  };
+  // this wavefront's chunk pair of every k-tile: chunks 2w (lanes 0-31) and 2w+1 (lanes 32-63)
+  const uint32_t frag = (uint32_t)(l32 * 128 + (((w * 2 + half) ^ ((lane >> 1) & 7)) << 4));
+
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#define VMCNT(n) ((((n) & 15) | 0x0F70 | (((n) >> 4) << 14)))
+  const int nk = (Kr + BK - 1) / BK;
+  gload(0); gload(1); gload(2);
+  for (int kt = 0; kt < nk; ++kt) {
+    // tile kt has landed once at most the loads of tiles kt+1 and kt+2 (two each) are outstanding
+    // A bare barrier between compiler-level memory fences: the workgroup release fence of __syncthreads() makes
+    // the wavefront wait for ALL outstanding LDS-direct loads, which would undo the prefetch.  What the barrier
+    // has to order is covered by hand: this wavefront's loads of tile kt by the vmcnt wait, its LDS reads of tile
+    // kt-1 by the lgkmcnt wait that precedes their MFMA.
+    __builtin_amdgcn_s_waitcnt(VMCNT(4));
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // every wavefront's part of tile kt is in LDS; all are done with tile kt-1
+    asm volatile("" ::: "memory");
+    // fragment reads as instructions, so that their completion is waited for exactly where written
+    const uint32_t sb = lds_base + (uint32_t)((kt & (NS - 1)) * STAGE) + frag;
+    u32x4 a, b;
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:4096" : "=&v"(a), "=&v"(b) : "v"(sb) : "memory");
+    gload(kt + 3);                 // into the stage tile kt-1 occupied
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b) : : "memory");
+    mma_chunk(acc, a, b, (T*)nullptr);
+  }
+  __builtin_amdgcn_s_waitcnt(VMCNT(0));
+#undef VMCNT
+  __syncthreads();                 // all stage reads and all (zero-fill) loads are over: the stages become the reduction buffer
+  float* red = (float*)smem;       // [4 wavefronts][16 registers][64 lanes]
+#pragma unroll
+  for (int r = 0; r < 16; ++r) red[(w * 16 + r) * 64 + lane] = acc[r];
+  __syncthreads();
+  // wavefront w finishes register quad w: rows 8w + 4*half .. +3 of column l32
+  float v[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float sum = red[(0 * 16 + 4 * w + e) * 64 + lane];
+#pragma unroll
+    for (int p = 1; p < 4; ++p) sum += red[(p * 16 + 4 * w + e) * 64 + lane];
+    v[e] = sum;
+  }
+  const int n = n0 + l32;
+  if (n < g.N) {
+    float bias = 0.0f;
+    if (EPI == EPI_FWD) bias = g.bias[n];
+    store_quad<T, EPI>(g, n, m0 + 8 * w + 4 * half, bias, v);
   }
 #endif
 }
@@ -317,8 +419,28 @@ hipError_t launch_cfg(int cfg, const GemmArgs& g, hipStream_t s) {
   }
 }
 
+template <typename T, int EPI>
+hipError_t launch_ksplit(const GemmArgs& g, hipStream_t s) {
+  const int tiles = ((g.M + 31) / 32) * ((g.N + 31) / 32);
+  hipLaunchKernelGGL((gemm_nt_ksplit_kernel<T, EPI>), dim3(tiles), dim3(256), 4 * 64 * 128, s, g);
+  return hipGetLastError();
+}
+
+// 64x64 tiles on fewer than this many workgroups: the contraction-split 32x32 variant fills the chip better
+constexpr long kKsplitBelowTiles = 128;
+bool use_ksplit(int M, int N) {
+  return (long)((M + 63) / 64) * ((N + 63) / 64) < kKsplitBelowTiles;
+}
+
 template <typename T>
 hipError_t launch_epi(int epi, int cfg, const GemmArgs& g, hipStream_t s) {
+  if (cfg == 2 && use_ksplit(g.M, g.N)) {
+    switch (epi) {
+      case EPI_FWD: return launch_ksplit<T, EPI_FWD>(g, s);
+      case EPI_DGRAD: return launch_ksplit<T, EPI_DGRAD>(g, s);
+      default: return launch_ksplit<T, EPI_WGRAD>(g, s);
+    }
+  }
   switch (epi) {
     case EPI_FWD: return launch_cfg<T, EPI_FWD>(cfg, g, s);
     case EPI_DGRAD: return launch_cfg<T, EPI_DGRAD>(cfg, g, s);
@@ -350,7 +472,9 @@ hipError_t gemm_configure_all() {
 
 const char* gemm_config_name(int dtype, int M, int N, int K) {
   (void)dtype; (void)K;
-  return kCfgs[pick_cfg(M, N)].name;
+  const int c = pick_cfg(M, N);
+  if (c == 2 && use_ksplit(M, N)) return "32x32 k-split";
+  return kCfgs[c].name;
 }
 
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs& g, hipStream_t s) {
