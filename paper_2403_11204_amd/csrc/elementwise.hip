@@ -27,7 +27,87 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---------------------------------------------------------------------------------
-// copy + transpose through a 64x64 LDS tile
+// 64x64 element tiles moved as 16-byte vectors
+// ---------------------------------------------------------------------------------
+// A tile row is CPR = 64/V chunks of V elements (V = 8 bf16 / 4 float).  Row-major traffic: lane -> (row,
+// chunk) with the chunk index fastest, so a wavefront touches whole 128-byte row segments.  Transposed
+// traffic: lane -> (column, chunk of V consecutive rows) with the row chunk fastest, the V values gathered
+// from LDS.  In LDS, chunk ch of row r sits at chunk position ch ^ ((r / V) mod CPR): the row-major writes
+// stay permutations within a row, and the gather of one wavefront instruction -- V-row groups 0..CPR-1 of a
+// few adjacent columns -- lands in distinct banks.
+template <typename T> struct Vec16;
+template <> struct Vec16<bf16> { typedef __attribute__((ext_vector_type(8))) __bf16 type; static constexpr int n = 8; };
+template <> struct Vec16<float> { typedef __attribute__((ext_vector_type(4))) float type; static constexpr int n = 4; };
+
+template <typename T>
+__device__ __forceinline__ int tile_slot(int row, int chunk) {     // position of a chunk in the LDS tile, in chunks
+  constexpr int V = Vec16<T>::n, CPR = 64 / V;
+  return row * CPR + (chunk ^ ((row / V) & (CPR - 1)));
+}
+
+// Writes the transposed tile: outT[c0 + c][r0 + r] for r below rows_t, from the LDS tile.
+template <typename T>
+__device__ __forceinline__ void store_tile_transposed(const typename Vec16<T>::type* tile, T* __restrict__ outT, int ldt,
+                                                      int r0, int c0, int rows_t, int C) {
+  typedef typename Vec16<T>::type vec_t;
+  constexpr int V = Vec16<T>::n, CPR = 64 / V, ITEMS = 64 * CPR / 256;
+  const T* flat = (const T*)tile;
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) {
+    const int idx = threadIdx.x + it * 256;
+    const int cl = idx / CPR, rc = idx % CPR;
+    const int c = c0 + cl, rs = r0 + rc * V;
+    if (c < C && rs < rows_t) {
+      vec_t o;
+#pragma unroll
+      for (int e = 0; e < V; ++e) o[e] = flat[tile_slot<T>(rc * V + e, cl / V) * V + (cl % V)];
+      *(vec_t*)(outT + (size_t)c * ldt + rs) = o;
+    }
+  }
+}
+
+// Needs: in/out/mask 16-byte aligned with leading dimensions that are multiples of V (a chunk never straddles
+// two rows; a chunk that straddles C reads pad elements of the same row, which callers keep allocated);
+// rows_t (rows written to the transposed output) a multiple of V or beyond the data (pad rows are zeros).
+template <typename T>
+__global__ __launch_bounds__(256) void copy_transpose_vec_kernel(const T* __restrict__ in, int ldin, int R, int C,
+                                                                 T* __restrict__ out, int ldo, T* __restrict__ outT,
+                                                                 int ldt, int rows_t, const T* __restrict__ mask,
+                                                                 int ldmask) {
+  typedef typename Vec16<T>::type vec_t;
+  constexpr int V = Vec16<T>::n, CPR = 64 / V, ITEMS = 64 * CPR / 256;
+  __shared__ vec_t tile[64 * CPR];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) {
+    const int idx = threadIdx.x + it * 256;
+    const int row = idx / CPR, ch = idx % CPR;
+    const int r = r0 + row, c = c0 + ch * V;
+    vec_t v;
+#pragma unroll
+    for (int e = 0; e < V; ++e) v[e] = from_f32<T>(0.0f);
+    if (r < R && c < C) {
+      v = *(const vec_t*)(in + (size_t)r * ldin + c);
+      if (mask) {     // optional ReLU mask: the element passes only where mask[r][c] > 0
+        const vec_t mk = *(const vec_t*)(mask + (size_t)r * ldmask + c);
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          if (!(to_f32<T>(mk[e]) > 0.0f)) v[e] = from_f32<T>(0.0f);
+      }
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (c + e >= C) v[e] = from_f32<T>(0.0f);     // pads stay zero
+      if (out) *(vec_t*)(out + (size_t)r * ldo + c) = v;
+    }
+    tile[tile_slot<T>(row, ch)] = v;
+  }
+  if (!outT) return;
+  __syncthreads();
+  store_tile_transposed<T>(tile, outT, ldt, r0, c0, rows_t, C);
+}
+
+// ---------------------------------------------------------------------------------
+// copy + transpose through a 64x64 LDS tile, element by element (any alignment)
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void copy_transpose_kernel(const T* __restrict__ in, int ldin, int R, int C,
@@ -66,34 +146,56 @@ __global__ __launch_bounds__(256) void mse_loss_grad_kernel(const T* __restrict_
                                                             int relu_last,
                                                             float scale, T* __restrict__ dZ, T* __restrict__ dZT, int ldt,
                                                             float* __restrict__ partials) {
-  __shared__ T tile[64][65];
+  typedef typename Vec16<T>::type vec_t;
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  constexpr int V = Vec16<T>::n, CPR = 64 / V, ITEMS = 64 * CPR / 256;
+  __shared__ vec_t tile[64 * CPR];
   __shared__ float red[4];
   const int b0 = blockIdx.y * 64, d0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const bool table_vec = (D & 3) == 0;        // label rows start 16-byte aligned
   float lsum = 0.0f;
-  for (int rr = ty; rr < 64; rr += 4) {
-    const int m = b0 + rr, i = d0 + tx;
-    T gv = from_f32<T>(0.0f);
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) {
+    const int idx = threadIdx.x + it * 256;
+    const int row = idx / CPR, ch = idx % CPR;
+    const int m = b0 + row, i = d0 + ch * V;
+    vec_t gv;
+#pragma unroll
+    for (int e = 0; e < V; ++e) gv[e] = from_f32<T>(0.0f);
     if (m < B && i < D) {
-      const float a = to_f32(AL[(size_t)m * ld + i]);
-      const int cls = min(max(y[m], 0), classes - 1);   // ids are the caller's; never index outside the table
-      const float d = a - table[(size_t)cls * D + i];
-      lsum += d * d;
-      const float g = (relu_last && !(a > 0.0f)) ? 0.0f : scale * d;
-      gv = from_f32<T>(g);
-      if (dZ) dZ[(size_t)m * ld + i] = gv;
+      const vec_t av = *(const vec_t*)(AL + (size_t)m * ld + i);     // a chunk that straddles D reads pad zeros
+      const int cls = min(max(y[m], 0), classes - 1);                 // ids are the caller's; never index outside the table
+      const float* trow = table + (size_t)cls * D + i;
+      float tv[V];
+      if (table_vec && i + V <= D) {
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q) {
+          const f32x4 t4 = *(const f32x4*)(trow + 4 * q);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) tv[4 * q + e] = t4[e];
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < V; ++e) tv[e] = i + e < D ? trow[e] : 0.0f;
+      }
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        if (i + e < D) {
+          const float a = to_f32<T>(av[e]);
+          const float d = a - tv[e];
+          lsum += d * d;
+          gv[e] = from_f32<T>((relu_last && !(a > 0.0f)) ? 0.0f : scale * d);
+        }
+      }
+      if (dZ) *(vec_t*)(dZ + (size_t)m * ld + i) = gv;
     }
-    tile[rr][tx] = gv;
+    tile[tile_slot<T>(row, ch)] = gv;
   }
   lsum = wave_sum(lsum);
-  if (tx == 0) red[ty] = lsum;
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = lsum;
   __syncthreads();
   if (threadIdx.x == 0) partials[blockIdx.y * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
-  const int B8 = (B + 7) & ~7;
-  for (int dd = ty; dd < 64; dd += 4) {
-    const int i = d0 + dd, m = b0 + tx;
-    if (i < D && m < B8) dZT[(size_t)i * ldt + m] = tile[tx][dd];
-  }
+  store_tile_transposed<T>(tile, dZT, ldt, b0, d0, (B + 7) & ~7, D);
 }
 
 // ---------------------------------------------------------------------------------
@@ -256,6 +358,21 @@ __global__ void bias_update_kernel(float* __restrict__ b, float* __restrict__ vb
 hipError_t launch_copy_transpose(int dtype, const void* in, int ldin, int R, int C, void* out, int ldo, void* outT,
                                  int ldt, int pad_t, const void* mask, int ldmask, hipStream_t s) {
   dim3 grid((C + 63) / 64, (R + 63) / 64);
+  // 16-byte vectors when every row of every operand starts on a 16-byte boundary and the transposed output takes
+  // whole row chunks; the element-wise kernel otherwise (a dense caller matrix whose width is not a multiple of V)
+  const int V = dtype == 1 ? 8 : 4;
+  const int rows_t = pad_t ? ((R + 7) & ~7) : R;
+  const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)outT | (uintptr_t)mask) & 15) == 0) && ldin % V == 0 &&
+                       (!out || ldo % V == 0) && (!outT || (ldt % V == 0 && rows_t % V == 0)) && (!mask || ldmask % V == 0);
+  if (aligned) {
+    if (dtype == 1)
+      copy_transpose_vec_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)in, ldin, R, C, (bf16*)out, ldo, (bf16*)outT, ldt, rows_t,
+                                                           (const bf16*)mask, ldmask);
+    else
+      copy_transpose_vec_kernel<float><<<grid, 256, 0, s>>>((const float*)in, ldin, R, C, (float*)out, ldo, (float*)outT, ldt,
+                                                            rows_t, (const float*)mask, ldmask);
+    return hipGetLastError();
+  }
   if (dtype == 1)
     copy_transpose_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)in, ldin, R, C, (bf16*)out, ldo, (bf16*)outT, ldt, pad_t,
                                                      (const bf16*)mask, ldmask);
