@@ -29,24 +29,21 @@ def f64(t):
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
-def test_comparison_config_segment_a_full_size():
-    widths, B, classes, lr = [784, 16384, 16384, 16384], 8192, 1000, 0.01
-    X, y = datagen.class_mean_inputs(B, classes, dim=784, seed=1)
-    table = orng.make_synthetic_labels(31, classes, widths[-1], orng.UNIFORM_PM1)
-    params = datagen.uniform_weights(widths, seed=17)
-
-    seg = api.Segment(widths, api.RELU_ALL, api.MSE_SIL, max_batch=B, dtype=api.BF16, lr=lr, momentum=0.9)
+def run_full_size(widths, act, loss, B, classes, Xd, y, table, params, lr=0.01):
+    """One step at full size on the device; sampled rows against the oracle chain; whole-batch properties."""
+    L = len(widths) - 1
+    seg = api.Segment(widths, act, loss, max_batch=B, dtype=api.BF16, lr=lr, momentum=0.9)
     for l, (W, b) in enumerate(params):
         seg.set_params(l, torch.from_numpy(W), torch.from_numpy(b))
-    seg.set_labels(torch.from_numpy(table).to(DEV))
-    Xd = torch.from_numpy(X).to(DEV).to(torch.bfloat16).contiguous()
+    if table is not None:
+        seg.set_labels(torch.from_numpy(table).to(DEV))
     yd = torch.from_numpy(y).to(DEV)
     loss_gpu = float(seg.step(Xd, yd).item())
     print("full-size step done, loss", loss_gpu, flush=True)
 
     # ---- sampled rows through the oracle chain ---------------------------------------
-    rows = np.array([0, 1, 4097, 8191])
-    ora = osg.Segment(widths, osg.RELU_ALL, osg.MSE_SIL, lr=lr, momentum=0.9, mode="bf16")
+    rows = np.array([0, 1, B // 2 + 1, B - 1])
+    ora = osg.Segment(widths, act, loss, lr=lr, momentum=0.9, mode="bf16")
     for l, (W, b) in enumerate(params):
         ora.set_params(l, W, b)
     Xrows = f64(Xd[torch.from_numpy(rows).to(DEV)])
@@ -54,15 +51,16 @@ def test_comparison_config_segment_a_full_size():
     print("oracle rows done", flush=True)
     ridx = torch.from_numpy(rows).to(DEV)
     flipped = np.zeros(len(rows), dtype=bool)
-    for l in range(3, 0, -1):
+    for l in range(L, 0, -1):
         a_got = f64(seg.get_activation(l, B)[ridx])
         a_ref = out["A"][l]
         assert np.max(np.abs(a_got - a_ref)) <= TOL * np.max(np.abs(a_ref)), ("A", l)
-        mism = (a_got > 0) != (a_ref > 0)
-        if mism.any():       # only near-ties of the oracle's pre-activation may be decided differently
-            assert np.all(np.abs(out["Z"][l][mism]) <= 1e-3 * np.max(np.abs(out["Z"][l]))), ("mask", l)
-            assert mism.mean() <= 1e-3
-            flipped |= mism.any(axis=1)
+        if l < L or act == api.RELU_ALL:
+            mism = (a_got > 0) != (a_ref > 0)
+            if mism.any():       # only near-ties of the oracle's pre-activation may be decided differently
+                assert np.all(np.abs(out["Z"][l][mism]) <= 1e-3 * np.max(np.abs(out["Z"][l]))), ("mask", l)
+                assert mism.mean() <= 1e-3
+                flipped |= mism.any(axis=1)
         dz_got = f64(seg.get_activation(l, B, kind=1)[ridx])
         dz_ref = out["dZ"][l]
         assert np.linalg.norm(dz_got - dz_ref) <= TOL * np.linalg.norm(dz_ref), ("dZ L2", l)
@@ -72,15 +70,18 @@ def test_comparison_config_segment_a_full_size():
     del ora, out
 
     # ---- properties over the whole batch ---------------------------------------------------
-    A = [None] + [seg.get_activation(l, B) for l in (1, 2, 3)]
-    A[0] = Xd
-    dZ = [None] + [seg.get_activation(l, B, kind=1) for l in (1, 2, 3)]
-    T = torch.from_numpy(table).to(DEV)[yd.long()]
-    diff = A[3].double() - T.double()
-    loss_def = float((diff * diff).mean().item())          # definition of the loss on the device's own output
+    A = [Xd] + [seg.get_activation(l, B) for l in range(1, L + 1)]
+    dZ = [None] + [seg.get_activation(l, B, kind=1) for l in range(1, L + 1)]
+    if loss == api.MSE_SIL:
+        T = torch.from_numpy(table).to(DEV)[yd.long()]
+        diff = A[L].double() - T.double()
+        loss_def = float((diff * diff).mean().item())      # definition of the loss on the device's own output
+    else:
+        Z = A[L].double()
+        loss_def = float((torch.logsumexp(Z, dim=1) - Z.gather(1, yd.long()[:, None])[:, 0]).mean().item())
     assert abs(loss_gpu - loss_def) <= 1e-5 * loss_def
     gen = torch.Generator(device="cpu").manual_seed(5)
-    for l in range(3):
+    for l in range(L):
         dW, db = seg.get_grads(l)
         r = torch.randn(widths[l], generator=gen, dtype=torch.float64).to(DEV)
         # dW r = dZ^T (A r): a wrong tile, a dropped k-slice or a transposed operand breaks this
@@ -97,3 +98,34 @@ def test_comparison_config_segment_a_full_size():
         vW, _ = seg.get_momentum(l)
         assert torch.equal(vW, dW)
         del dW, Wn, W0, expect, vW
+    del seg
+    torch.cuda.empty_cache()
+
+
+def test_comparison_config_segment_a_full_size():
+    widths, B, classes = [784, 16384, 16384, 16384], 8192, 1000
+    X, y = datagen.class_mean_inputs(B, classes, dim=784, seed=1)
+    table = orng.make_synthetic_labels(31, classes, widths[-1], orng.UNIFORM_PM1)
+    Xd = torch.from_numpy(X).to(DEV).to(torch.bfloat16).contiguous()
+    run_full_size(widths, api.RELU_ALL, api.MSE_SIL, B, classes, Xd, y, table, datagen.uniform_weights(widths, seed=17))
+
+
+def test_comparison_config_segment_b_full_size():
+    # the final segment: inputs are the cut's label of the class plus noise, 1000-way cross-entropy (its last
+    # layer is the skinny product, 1000 columns)
+    widths, B, classes = [16384, 16384, 16384, 1000], 8192, 1000
+    _, y = datagen.class_mean_inputs(B, classes, dim=784, seed=1)
+    cut = api.make_synthetic_labels(31, classes, widths[0], api.UNIFORM_PM1, 1.0, api.F32)
+    Xd = api.make_segment_inputs(6, cut, torch.from_numpy(y).to(DEV), 0, 0.05, api.BF16)
+    run_full_size(widths, api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, B, classes, Xd, y, None,
+                  datagen.uniform_weights(widths, seed=18))
+
+
+def test_deep_config_interior_segment_full_size():
+    # an interior segment of the 12-layer configuration: 8192-8192-8192-8192, batch 4096, N(0,1) labels
+    widths, B, classes = [8192, 8192, 8192, 8192], 4096, 100
+    _, y = datagen.class_mean_inputs(B, classes, dim=784, seed=1)
+    cut = api.make_synthetic_labels(21, classes, widths[0], api.NORMAL, 1.0, api.F32)
+    Xd = api.make_segment_inputs(6, cut, torch.from_numpy(y).to(DEV), 0, 0.05, api.BF16)
+    table = orng.make_synthetic_labels(22, classes, widths[-1], orng.NORMAL)
+    run_full_size(widths, api.RELU_ALL, api.MSE_SIL, B, classes, Xd, y, table, datagen.uniform_weights(widths, seed=19))
