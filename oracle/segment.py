@@ -146,21 +146,45 @@ class Segment:
         return loss, G
 
     # -- one training step ---------------------------------------------------------
-    def step(self, X, y, table=None, update=True, full_batch=None):
+    def step(self, X, y, table=None, update=True, full_batch=None, tie_decisions=None, tie_band=1e-3):
         """Forward, loss, backward, SGD.  Returns a dict with everything a
         parity test wants to look at (values *before* the update for A, Z, dZ,
         dW, db; parameters are updated in place).  With ``full_batch`` the rows
         are a sample of a larger batch: A, Z and dZ of those rows are exact (they
         depend on the rest of the batch only through its size); loss is then these
-        rows' share, dW and db are not formed and no update may be asked for."""
+        rows' share, dW and db are not formed and no update may be asked for.
+
+        ``tie_decisions``: whether a ReLU unit passes gradient is an integer decided
+        from a floating-point pre-activation; where that value is zero to within
+        rounding, "active" and "inactive" are both correct, and two correct
+        implementations may differ.  tie_decisions[l] (l = 1..L, boolean, shape of
+        A[l]) holds another implementation's decisions; they are taken over ONLY
+        where this oracle's own pre-activation is within tie_band * max|Z_l| of
+        zero.  The result reports how many decisions were taken over ("ties_taken")
+        and how many disagreements lie outside the band ("decisions_refused": those
+        are the other side's errors, and the oracle keeps its own decision there)."""
         assert full_batch is None or not update
         Wp = self._weights_for_products()
         A, Z = self.forward_all(X)
         loss, G = self.loss_and_grad(A[self.L], y, table, full_batch)
+        ties_taken, refused = 0, 0
+
+        def active(l):
+            nonlocal ties_taken, refused
+            own = A[l] > 0.0
+            if tie_decisions is None or tie_decisions[l] is None:
+                return own
+            other = np.asarray(tie_decisions[l], dtype=bool)
+            differ = own != other
+            near = np.abs(Z[l]) <= tie_band * np.max(np.abs(Z[l]))
+            ties_taken += int(np.sum(differ & near))
+            refused += int(np.sum(differ & ~near))
+            return np.where(near, other, own)
+
         dZ = [None] * (self.L + 1)
         dW = [None] * self.L
         db = [None] * self.L
-        g = G * (A[self.L] > 0.0) if self._relu_on(self.L) else G
+        g = G * active(self.L) if self._relu_on(self.L) else G
         dZ[self.L] = self._store(g)
         for l in range(self.L, 0, -1):
             if full_batch is None:       # parameter gradients need every row of the batch
@@ -168,7 +192,7 @@ class Segment:
                 db[l - 1] = dZ[l].sum(axis=0)
             if l > 1:
                 dA = dZ[l] @ Wp[l - 1]
-                dZ[l - 1] = self._store(dA * (A[l - 1] > 0.0))
+                dZ[l - 1] = self._store(dA * active(l - 1))
         if update:
             for l in range(self.L):
                 self.vW[l] = self.mu * self.vW[l] + dW[l]
@@ -178,7 +202,8 @@ class Segment:
                 if self.mode == "bf16":     # master parameters live in float32
                     self.W[l] = self.W[l].astype(np.float32).astype(np.float64)
                     self.b[l] = self.b[l].astype(np.float32).astype(np.float64)
-        return {"loss": loss, "A": A, "Z": Z, "dZ": dZ, "dW": dW, "db": db}
+        return {"loss": loss, "A": A, "Z": Z, "dZ": dZ, "dW": dW, "db": db, "ties_taken": ties_taken,
+                "decisions_refused": refused}
 
 
 # -- recovery phase (paper Sec. 5) ---------------------------------------------------

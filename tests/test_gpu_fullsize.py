@@ -4,7 +4,8 @@ the benchmark times (784-16384-16384-16384, bf16, batch 8192, 256x256 tiles).
 A full oracle step at this size is ~27 TFLOP of float64 work, so:
   * sampled batch rows are pushed through the oracle's whole forward and backward
     chain (a row of A_l / dZ_l depends on the other rows only through the batch
-    size in the means) and compared element by element;
+    size in the means) and compared element by element (ReLU decisions at
+    pre-activations that are zero to within rounding are taken over from the device);
   * what needs every row (loss, dW, db, the update) is checked through properties
     that hold at any size: the loss against its definition on the device's own
     output, dW and db against random projections / column sums of the device's own
@@ -47,26 +48,20 @@ def run_full_size(widths, act, loss, B, classes, Xd, y, table, params, lr=0.01):
     for l, (W, b) in enumerate(params):
         ora.set_params(l, W, b)
     Xrows = f64(Xd[torch.from_numpy(rows).to(DEV)])
-    out = ora.step(Xrows, y[rows], table, update=False, full_batch=B)
-    print("oracle rows done", flush=True)
     ridx = torch.from_numpy(rows).to(DEV)
-    flipped = np.zeros(len(rows), dtype=bool)
+    acts = [None] + [f64(seg.get_activation(l, B)[ridx]) for l in range(1, L + 1)]
+    # ReLU decisions at pre-activations that are zero to within rounding are taken over from the device
+    # (both answers are correct there); anywhere else a disagreement is an error
+    out = ora.step(Xrows, y[rows], table, update=False, full_batch=B, tie_decisions=[None] + [a > 0 for a in acts[1:]])
+    print("oracle rows done, ties taken", out["ties_taken"], flush=True)
+    assert out["decisions_refused"] == 0
+    assert out["ties_taken"] <= max(1, int(1e-3 * sum(a.size for a in acts[1:])))
     for l in range(L, 0, -1):
-        a_got = f64(seg.get_activation(l, B)[ridx])
         a_ref = out["A"][l]
-        assert np.max(np.abs(a_got - a_ref)) <= TOL * np.max(np.abs(a_ref)), ("A", l)
-        if l < L or act == api.RELU_ALL:
-            mism = (a_got > 0) != (a_ref > 0)
-            if mism.any():       # only near-ties of the oracle's pre-activation may be decided differently
-                assert np.all(np.abs(out["Z"][l][mism]) <= 1e-3 * np.max(np.abs(out["Z"][l]))), ("mask", l)
-                assert mism.mean() <= 1e-3
-                flipped |= mism.any(axis=1)
+        assert np.max(np.abs(acts[l] - a_ref)) <= TOL * np.max(np.abs(a_ref)), ("A", l)
         dz_got = f64(seg.get_activation(l, B, kind=1)[ridx])
         dz_ref = out["dZ"][l]
-        assert np.linalg.norm(dz_got - dz_ref) <= TOL * np.linalg.norm(dz_ref), ("dZ L2", l)
-        keep = ~flipped
-        if keep.any():
-            assert np.max(np.abs(dz_got[keep] - dz_ref[keep])) <= TOL * np.max(np.abs(dz_ref)), ("dZ", l)
+        assert np.max(np.abs(dz_got - dz_ref)) <= TOL * np.max(np.abs(dz_ref)), ("dZ", l)
     del ora, out
 
     # ---- properties over the whole batch ---------------------------------------------------

@@ -107,30 +107,23 @@ def check_step(g, o, X, y, table_np, dtype, steps=1, check_internals=True):
     W_before = [o.W[l].copy() for l in range(o.L)]
     for s in range(steps):
         loss_g = float(g.step(Xd, yd).item())
-        out = o.step(Xv, y, table_np)
+        # The ReLU mask is an integer decision taken from a floating-point value.  Where the oracle's
+        # pre-activation is zero to within rounding, "active" and "inactive" are both correct, and one such
+        # element changes the whole row of every dZ below it and a row of dW.  So the oracle takes over the
+        # device's decisions -- only inside a narrow band around zero -- and everything after is compared
+        # element by element; a disagreement outside the band is the device's error, and decisions taken
+        # over must be rare.
+        acts = [None] + [to_np(g.get_activation(l, B)) for l in range(1, o.L + 1)]
+        out = o.step(Xv, y, table_np, tie_decisions=[None] + [a > 0 for a in acts[1:]])
         assert abs(loss_g - out["loss"]) <= tol * abs(out["loss"]), (s, loss_g, out["loss"])
+        assert out["decisions_refused"] == 0
+        assert out["ties_taken"] <= max(1, int(1e-4 * sum(a.size for a in acts[1:]))), out["ties_taken"]
     if check_internals:      # state of the last step
-        # The ReLU mask is an integer decision taken from a floating-point value.  Where the
-        # oracle's pre-activation is a near-tie the two sides may legitimately decide
-        # differently; such an element is valid on both sides, but it changes the whole row of
-        # every dZ below it.  So: every disagreement must be a near-tie and they must be rare;
-        # rows that contain one are compared in the L2 sense only, all other rows element-wise.
-        flipped_rows = np.zeros(B, dtype=bool)
         for l in range(o.L, 0, -1):
-            a_got = to_np(g.get_activation(l, B)).astype(np.float64)
-            assert rel_err(a_got, out["A"][l]) <= tol, ("A", l)
-            if l < o.L or o.act == osg.RELU_ALL:
-                mism = (a_got > 0) != (out["A"][l] > 0)
-                if mism.any():
-                    assert np.all(np.abs(out["Z"][l][mism]) <= 1e-3 * np.max(np.abs(out["Z"][l]))), ("mask", l)
-                    assert mism.mean() <= 1e-4, ("mask rate", l, mism.mean())
-                    flipped_rows |= mism.any(axis=1)
+            assert rel_err(acts[l], out["A"][l]) <= tol, ("A", l)
             dz_ref = out["dZ"][l]
             dz_got = to_np(g.get_activation(l, B, kind=1)).astype(np.float64)
-            assert np.linalg.norm(dz_got - dz_ref) <= tol * np.linalg.norm(dz_ref), ("dZ L2", l)
-            keep = ~flipped_rows
-            assert keep.mean() >= 0.9
-            assert np.max(np.abs(dz_got[keep] - dz_ref[keep])) <= tol * np.max(np.abs(dz_ref)), ("dZ", l)
+            assert rel_err(dz_got, dz_ref) <= tol, ("dZ", l)
         for l in range(o.L):
             dW, db = g.get_grads(l)
             assert rel_err(to_np(dW), out["dW"][l]) <= tol, ("dW", l)
@@ -200,6 +193,32 @@ def test_several_steps_with_momentum(dtype):
     g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, dtype, max_batch=128, lr=0.02, mom=0.9, wseed=6)
     X, y, table = case_data(widths, api.MSE_SIL, 128, api.UNIFORM01, 20, seed=4)
     check_step(g, o, X, y, table, dtype, steps=5, check_internals=(dtype == api.F32))
+
+
+@pytest.mark.parametrize("widths,B", [([1024, 2048, 1024], 2048), ([256, 4096, 4096], 4096)], ids=["tiles128", "tiles256"])
+def test_float32_products_on_the_larger_tiles(widths, B):
+    # float32 through the 128x128 and the 256x256 tile instantiations (forward, data gradient, weight gradient)
+    X, y, table = case_data(widths, api.MSE_SIL, B, api.UNIFORM_PM1, 31, seed=8)
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, api.F32, max_batch=B, lr=0.01, mom=0.9, wseed=9)
+    check_step(g, o, X, y, table, api.F32)
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+def test_degenerate_shapes(dtype):
+    # one sample; one unit per layer; one class (cross-entropy over a single class is 0 with zero gradient)
+    X, y, table = case_data([5, 7, 3], api.MSE_SIL, 1, api.NORMAL, 4, seed=3)
+    g, o = make_pair([5, 7, 3], api.RELU_ALL, api.MSE_SIL, dtype, max_batch=1, lr=0.1, mom=0.9, wseed=2)
+    check_step(g, o, X, y, table, dtype)
+    X, y, table = case_data([1, 1, 1], api.MSE_SIL, 17, api.UNIFORM01, 3, seed=3)
+    g, o = make_pair([1, 1, 1], api.RELU_ALL, api.MSE_SIL, dtype, max_batch=17, lr=0.1, mom=0.0, wseed=4)
+    check_step(g, o, X, y, table, dtype)
+    X, y, _ = case_data([6, 4, 1], api.SOFTMAX_XENT, 9, None, 1, seed=3)
+    g, o = make_pair([6, 4, 1], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, dtype, max_batch=9, lr=0.1, mom=0.9, wseed=5)
+    W_before = [g.get_params(l)[0].clone() for l in range(2)]
+    loss = g.step(as_input(X, dtype)[0], torch.from_numpy(y).to(DEV))
+    assert float(loss.item()) == 0.0
+    for l in range(2):
+        assert torch.equal(g.get_params(l)[0], W_before[l])
 
 
 def test_wide_bf16_config_one_step():

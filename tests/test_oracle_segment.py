@@ -426,3 +426,35 @@ def test_recovery_steps_against_autodiff_library():
             assert np.allclose(left.b[l], tl[l][1].detach().numpy(), rtol=1e-11, atol=1e-15)
     for l in range(2):
         assert np.array_equal(right.W[l], right_before[l])   # frozen
+
+
+# ---------------------------------------------------------------------------------
+# ReLU decisions at ties
+# ---------------------------------------------------------------------------------
+def test_tie_decisions_are_taken_only_inside_the_band():
+    # hand-built 2-2-1 net: unit 0 of layer 1 has pre-activation exactly 0 for sample 0 (a tie), everything else is clear
+    seg = osg.Segment([2, 2, 1], osg.RELU_HIDDEN_IDENTITY_LAST, osg.MSE_SIL, lr=0.1, momentum=0.0)
+    seg.set_params(0, np.array([[1.0, -1.0], [0.5, 0.5]]), np.array([0.0, 0.0]))
+    seg.set_params(1, np.array([[2.0, 3.0]]), np.array([0.0]))
+    X = np.array([[1.0, 1.0], [2.0, 1.0]])        # Z1 = [[0, 1], [1, 1.5]]
+    y = np.array([0, 0])
+    T = np.array([[0.0]])
+    own = seg.step(X, y, T, update=False)
+    assert np.array_equal(own["Z"][1], np.array([[0.0, 1.0], [1.0, 1.5]]))
+    # own decision at the tie: inactive (the derivative of ReLU at 0 is taken as 0)
+    # out = [3, 6.5]; G = 2*(out - 0)/2 = out; dZ1 = G * W2 * mask
+    assert np.array_equal(own["dZ"][1], np.array([[0.0, 9.0], [13.0, 19.5]]))
+    same = seg.step(X, y, T, update=False, tie_decisions=[None, own["A"][1] > 0, None])
+    assert same["ties_taken"] == 0 and same["decisions_refused"] == 0
+    assert np.array_equal(same["dZ"][1], own["dZ"][1])
+    # the other side calls the tie "active": taken over, the gradient flows through that unit
+    other = np.array([[True, True], [True, True]])
+    took = seg.step(X, y, T, update=False, tie_decisions=[None, other, None])
+    assert took["ties_taken"] == 1 and took["decisions_refused"] == 0
+    assert np.array_equal(took["dZ"][1], np.array([[6.0, 9.0], [13.0, 19.5]]))
+    assert np.array_equal(took["dW"][0], took["dZ"][1].T @ X)
+    # a disagreement at a clear pre-activation (1.5, far outside the band) is refused and counted
+    wrong = np.array([[False, True], [True, False]])
+    ref = seg.step(X, y, T, update=False, tie_decisions=[None, wrong, None])
+    assert ref["ties_taken"] == 0 and ref["decisions_refused"] == 1
+    assert np.array_equal(ref["dZ"][1], own["dZ"][1])
