@@ -76,26 +76,50 @@ template <typename T> struct Vec4;
 template <> struct Vec4<bf16> { typedef bf16x4 type; };
 template <> struct Vec4<float> { typedef f32x4 type; };
 
-// Epilogue of four consecutive rows mb..mb+3 of output column n (one accumulator register quad).
-//   EPI_FWD  : + bias, optional ReLU;  EPI_DGRAD: zero where the mask (stored transposed) is not positive;
-//   both store row-major C and/or transposed CT in T (the transposed store is one vector; rows past M up to
-//   the next multiple of 8 are written as zero there);  EPI_WGRAD: float32 row-major.
+// 4x4 transpose across the 4 lanes of a quad (lanes 4g..4g+3): on return, lane i holds in v[j] what lane j held
+// in v[i].  Two butterfly stages of quad-permute DPP moves; every lane of the quad must be active.
+__device__ __forceinline__ float quad_xor(float x, bool by_two) {
+  const int xi = __builtin_bit_cast(int, x);
+  const int r = by_two ? __builtin_amdgcn_update_dpp(0, xi, 0x4E, 0xF, 0xF, true)      // lanes [2,3,0,1]
+                       : __builtin_amdgcn_update_dpp(0, xi, 0xB1, 0xF, 0xF, true);     // lanes [1,0,3,2]
+  return __builtin_bit_cast(float, r);
+}
+__device__ __forceinline__ void quad_transpose(float (&v)[4], int lane) {
+  const bool b0 = lane & 1, b1 = lane & 2;
+  float r;
+  r = quad_xor(b0 ? v[0] : v[1], false); if (b0) v[0] = r; else v[1] = r;
+  r = quad_xor(b0 ? v[2] : v[3], false); if (b0) v[2] = r; else v[3] = r;
+  r = quad_xor(b1 ? v[0] : v[2], true);  if (b1) v[0] = r; else v[2] = r;
+  r = quad_xor(b1 ? v[1] : v[3], true);  if (b1) v[1] = r; else v[3] = r;
+}
+
+// Epilogue of one accumulator register quad: rows mb..mb+3 of output column n, v[e] = row mb+e.  The 4 lanes of
+// a quad hold 4 consecutive columns (n - lane%4 is a multiple of 4), and a lane whose column is past N takes part
+// with zeros: nothing here may diverge inside a quad before the transpose.
+//   EPI_FWD  : + bias (the caller passes 0 for a column past N), optional ReLU;
+//   EPI_DGRAD: zero where the mask (stored transposed) is not positive;
+//   both store transposed CT in T as one vector per lane (4 rows of its column; rows past M up to the next
+//   multiple of 8 are written as zero) and row-major C after a 4x4 transpose inside the quad, so that a lane
+//   stores 4 consecutive columns of one row as one vector (pad columns up to the leading dimension receive
+//   zeros);  EPI_WGRAD: float32 row-major, same transposed vector store.
 template <typename T, int EPI>
-__device__ __forceinline__ void store_quad(const GemmArgs& g, int n, int mb, float bias, float (&v)[4]) {
+__device__ __forceinline__ void store_quad(const GemmArgs& g, int n, int mb, float bias, float (&v)[4], int lane) {
+  typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+  const bool col_ok = n < g.N;
+  const int row = mb + (lane & 3), nb = n - (lane & 3);      // after the transpose: this lane's row, first of its 4 columns
   if (EPI == EPI_WGRAD) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (mb + e < g.M) g.Cf[(size_t)(mb + e) * g.ldc + n] = v[e];
+    quad_transpose(v, lane);
+    if (row < g.M && nb < g.N) *(f32x4_t*)(g.Cf + (size_t)row * g.ldc + nb) = f32x4_t{v[0], v[1], v[2], v[3]};
     return;
   }
-  if (mb >= ((g.M + 7) & ~7)) return;
+  if (mb >= ((g.M + 7) & ~7)) return;       // the same for the whole quad
   if (EPI == EPI_FWD) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       v[e] += bias;
       if (g.relu) v[e] = fmaxf(v[e], 0.0f);
     }
-  } else if (g.maskT) {   // no mask: the gradient w.r.t. the segment input
+  } else if (g.maskT && col_ok) {   // no mask: the gradient w.r.t. the segment input
     typedef typename Vec4<T>::type mvec_t;
     const mvec_t mk = *(const mvec_t*)((const T*)g.maskT + (size_t)n * g.ldmask + mb);
 #pragma unroll
@@ -104,17 +128,21 @@ __device__ __forceinline__ void store_quad(const GemmArgs& g, int n, int mb, flo
   }
 #pragma unroll
   for (int e = 0; e < 4; ++e)
-    if (mb + e >= g.M) v[e] = 0.0f;
-  if (g.C) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (mb + e < g.M) ((T*)g.C)[(size_t)(mb + e) * g.ldc + n] = (T)v[e];
-  }
-  if (g.CT) {
+    if (mb + e >= g.M || !col_ok) v[e] = 0.0f;
+  if (g.CT && col_ok) {
     typename Vec4<T>::type o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = (T)v[e];
     *(typename Vec4<T>::type*)((T*)g.CT + (size_t)n * g.ldct + mb) = o;
+  }
+  if (g.C) {
+    quad_transpose(v, lane);
+    if (row < g.M && nb < g.N) {
+      typename Vec4<T>::type o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (T)v[e];
+      *(typename Vec4<T>::type*)((T*)g.C + (size_t)row * g.ldc + nb) = o;
+    }
   }
 }
 
@@ -259,9 +287,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int n = n0 + wn * WTN + j * 32 + l32;
-    if (n >= g.N) continue;
     float bias = 0.0f;
-    if (EPI == EPI_FWD) bias = g.bias[n];
+    if (EPI == EPI_FWD && n < g.N) bias = g.bias[n];
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -269,7 +296,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-        store_quad<T, EPI>(g, n, m0 + wm * WTM + i * 32 + 8 * q + 4 * half, bias, v);
+        store_quad<T, EPI>(g, n, m0 + wm * WTM + i * 32 + 8 * q + 4 * half, bias, v, lane);
         // keep the scheduler from hoisting every block's address arithmetic and mask
         // loads to the top of the epilogue (that spills registers)
         __builtin_amdgcn_sched_barrier(0);
@@ -366,11 +393,9 @@ __global__ __launch_bounds__(256) void gemm_nt_ksplit_kernel(const GemmArgs g) {
     v[e] = sum;
   }
   const int n = n0 + l32;
-  if (n < g.N) {
-    float bias = 0.0f;
-    if (EPI == EPI_FWD) bias = g.bias[n];
-    store_quad<T, EPI>(g, n, m0 + 8 * w + 4 * half, bias, v);
-  }
+  float bias = 0.0f;
+  if (EPI == EPI_FWD && n < g.N) bias = g.bias[n];
+  store_quad<T, EPI>(g, n, m0 + 8 * w + 4 * half, bias, v, lane);
 #endif
 }
 
