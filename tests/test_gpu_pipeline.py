@@ -107,3 +107,44 @@ def test_two_phase_training_recovery_and_join_tiny_config():
     assert abs(acc - ref_acc) <= 0.005
     logits = to_np(pipeline.joined_forward([gl, gr], Xd, 64))
     assert rel_err(logits, ref_logits) <= 1e-3
+
+
+def test_segments_stepping_concurrently_on_separate_streams():
+    # independent segments are independent jobs (Sec. 2.1): four of them stepping at once on four streams of
+    # the one device must end exactly where the same four end when run one after another
+    specs = [([96, 160, 64], api.RELU_ALL, api.MSE_SIL), ([64, 200, 64], api.RELU_ALL, api.MSE_SIL),
+             ([64, 72, 64], api.RELU_ALL, api.MSE_SIL), ([64, 130, 10], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT)]
+    B, classes = 300, 10
+    X0, y = datagen.class_mean_inputs(B, classes, dim=96, seed=2)
+    yd = torch.from_numpy(y).to(DEV)
+    tables = [api.make_synthetic_labels(40 + i, classes, 64, api.NORMAL) for i in range(3)]
+    inputs = [torch.from_numpy(X0).to(DEV).to(torch.bfloat16).contiguous()]
+    inputs += [api.make_segment_inputs(50 + i, tables[i], yd, 0, 0.05, api.BF16) for i in range(3)]
+
+    def build():
+        segs = []
+        for i, (w, act, loss) in enumerate(specs):
+            s = api.Segment(w, act, loss, max_batch=B, dtype=api.BF16, lr=0.05, momentum=0.9)
+            s.init(70 + i)
+            if loss == api.MSE_SIL:
+                s.set_labels(tables[i])
+            segs.append(s)
+        return segs
+
+    serial, parallel = build(), build()
+    for _ in range(3):
+        for s, x in zip(serial, inputs):
+            s.step(x, yd)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in specs]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    for _ in range(3):
+        for s, x, st in zip(parallel, inputs, streams):
+            with torch.cuda.stream(st):
+                s.step(x, yd)
+    torch.cuda.synchronize()
+    for a, b in zip(serial, parallel):
+        for l in range(a.L):
+            (Wa, ba), (Wb, bb) = a.get_params(l), b.get_params(l)
+            assert torch.equal(Wa, Wb) and torch.equal(ba, bb)
