@@ -27,8 +27,9 @@
 //     ~13 cycles per wavefront instruction; measured, it was the largest stall).
 //     Out-of-range rows and k-tail chunks read as zero through the buffer resource's
 //     range check, so ragged M, N and K need no branches.
-//   * two LDS stages of (BM+BN) x 128 bytes; the loads of tile k+2 are issued as soon as
-//     the barrier after sub-step 2 of tile k has freed its stage; one barrier per k-tile.
+//   * NS LDS stages of (BM+BN) x 128 bytes (two for the 256x256 tile, four for the small ones); the
+//     loads of tile k+NS are issued as soon as the barrier after sub-step 2 of tile k has freed
+//     its stage; one barrier per k-tile.
 //   * every k-tile is 4 sub-steps of MIxNI MFMAs; the fragments of sub-step s+1 are read
 //     from LDS while sub-step s multiplies, and the source order "2 LDS reads, 2 loads,
 //     2 MFMAs" is pinned with scheduling fences, because the compiler's own schedule
@@ -146,7 +147,7 @@ __device__ __forceinline__ void store_quad(const GemmArgs& g, int n, int mb, flo
   }
 }
 
-template <typename T, int BM, int BN, int EPI, int NW>
+template <typename T, int BM, int BN, int EPI, int NW, int NS>
 __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)   // LDS-direct builtins exist in the device pass only; the host pass needs just the launch stub
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -242,16 +243,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 
   const int nk = (Kr + BK - 1) / BK;
 #pragma unroll
-  for (int i = 0; i < NLD; ++i) gload_one(0, 0, i);
+  for (int st = 0; st < NS; ++st)
 #pragma unroll
-  for (int i = 0; i < NLD; ++i) gload_one(1, 1, i);
-  __builtin_amdgcn_s_waitcnt(VMCNT(NLD));
+    for (int i = 0; i < NLD; ++i) gload_one(st, st, i);
+  __builtin_amdgcn_s_waitcnt(VMCNT((NS - 1) * NLD));
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < NRD; ++r) read_one(0, 0, 0, r);
   auto rd_lo = [](int g) { return 2 * g < NRD ? 2 * g : NRD; };
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1, nxt = cur ^ 1;
+    const int cur = kt % NS, nxt = (kt + 1) % NS;
 #pragma unroll
     for (int kk = 0; kk < 3; ++kk) {
 #pragma unroll
@@ -264,14 +265,24 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
       }
     }
     // tile kt+1 must have landed in stage nxt (this wave's part), and every wave must be done reading stage cur
-    __builtin_amdgcn_s_waitcnt(VMCNT(0));
-    __syncthreads();
+    if (NS == 2) {
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));
+      __syncthreads();
+    } else {
+      // tiles kt+2 .. kt+NS-1 stay in flight.  A bare barrier between compiler fences: the workgroup release fence
+      // of __syncthreads() waits for EVERY outstanding LDS-direct load.  What the barrier has to order is waited for
+      // by hand: this wavefront's loads of tile kt+1 (vmcnt) and its LDS reads of stage cur (lgkmcnt 0).
+      __builtin_amdgcn_s_waitcnt(VMCNT((NS - 2) * NLD) & 0xF0FF);
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    }
 #pragma unroll
     for (int g = 0; g < NRD; ++g) {
 #pragma unroll
       for (int r = rd_lo(g); r < rd_lo(g + 1); ++r) read_one(nxt, 0, 0, r);
 #pragma unroll
-      for (int i = g * NLD / NRD; i < (g + 1) * NLD / NRD; ++i) gload_one(kt + 2, cur, i);
+      for (int i = g * NLD / NRD; i < (g + 1) * NLD / NRD; ++i) gload_one(kt + NS, cur, i);
 #pragma unroll
       for (int m = g * NMM / NRD; m < (g + 1) * NMM / NRD; ++m) mma_one(1, m);
       SLP_FENCE();
@@ -402,45 +413,57 @@ __global__ __launch_bounds__(256) void gemm_nt_ksplit_kernel(const GemmArgs g) {
 // ---- host side -------------------------------------------------------------------------------
 struct TileCfg { int bm, bn; const char* name; };
 const TileCfg kCfgs[3] = {{256, 256, "256x256"}, {128, 128, "128x128"}, {64, 64, "64x64"}};
+constexpr int kCfg128TwoStage = 3;
+
+long tiles_of(int M, int N, int c) {
+  return (long)((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
+}
 
 int pick_cfg(int M, int N) {
   // largest tile that still gives every compute unit (256 of them) work
-  for (int c = 0; c < 3; ++c) {
-    const long tiles = (long)((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
-    if (tiles >= 224) return c;
-  }
+  for (int c = 0; c < 3; ++c)
+    if (tiles_of(M, N, c) >= 224) {
+      // 128x128 with two 32 KB stages lets two workgroups share a compute unit; with 512 or more tiles that hides
+      // more latency than four stages of one workgroup do (measured 880 against 730 TFLOP/s on 8192x1000x16384),
+      // with fewer tiles the four stages win (681 -> 812 TFLOP/s on 1024x4096x4096)
+      if (c == 1 && tiles_of(M, N, 1) >= 512) return kCfg128TwoStage;
+      return c;
+    }
   return 2;
 }
 
-template <typename T, int BM, int BN, int EPI, int NW>
+template <typename T, int BM, int BN, int EPI, int NW, int NS>
 hipError_t configure_one() {
-  constexpr int smem = 2 * (BM + BN) * 128;
+  constexpr int smem = NS * (BM + BN) * 128;
   static bool configured = false;   // one attribute call per instantiation
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_nt_kernel<T, BM, BN, EPI, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_nt_kernel<T, BM, BN, EPI, NW, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     configured = true;
   }
   return hipSuccess;
 }
 
-template <typename T, int BM, int BN, int EPI, int NW>
+template <typename T, int BM, int BN, int EPI, int NW, int NS>
 hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
-  constexpr int smem = 2 * (BM + BN) * 128;
-  auto kern = gemm_nt_kernel<T, BM, BN, EPI, NW>;
-  hipError_t e = configure_one<T, BM, BN, EPI, NW>();
+  constexpr int smem = NS * (BM + BN) * 128;
+  auto kern = gemm_nt_kernel<T, BM, BN, EPI, NW, NS>;
+  hipError_t e = configure_one<T, BM, BN, EPI, NW, NS>();
   if (e != hipSuccess) return e;
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * 64), smem, s, g);
   return hipGetLastError();
 }
 
+// LDS stages (loads run stages-1 k-tiles ahead of the multiplies): a 256x256 tile fills LDS with two, and its k-tile
+// is ~1 us of MFMAs, enough to cover the loads of the next one; the k-tiles of the small tiles are 4-16x shorter.
 template <typename T, int EPI>
 hipError_t launch_cfg(int cfg, const GemmArgs& g, hipStream_t s) {
   switch (cfg) {
-    case 0: return launch_one<T, 256, 256, EPI, 8>(g, s);
-    case 1: return launch_one<T, 128, 128, EPI, 4>(g, s);
-    default: return launch_one<T, 64, 64, EPI, 4>(g, s);
+    case 0: return launch_one<T, 256, 256, EPI, 8, 2>(g, s);
+    case 1: return launch_one<T, 128, 128, EPI, 4, 4>(g, s);
+    case kCfg128TwoStage: return launch_one<T, 128, 128, EPI, 4, 2>(g, s);
+    default: return launch_one<T, 64, 64, EPI, 4, 4>(g, s);
   }
 }
 
@@ -459,7 +482,7 @@ bool use_ksplit(int M, int N) {
 
 template <typename T>
 hipError_t launch_epi(int epi, int cfg, const GemmArgs& g, hipStream_t s) {
-  if (cfg == 2 && use_ksplit(g.M, g.N)) {
+  if (cfg == 2 && use_ksplit(g.M, g.N)) {   // (pick_cfg returns 2 for everything small)
     switch (epi) {
       case EPI_FWD: return launch_ksplit<T, EPI_FWD>(g, s);
       case EPI_DGRAD: return launch_ksplit<T, EPI_DGRAD>(g, s);
@@ -475,9 +498,10 @@ hipError_t launch_epi(int epi, int cfg, const GemmArgs& g, hipStream_t s) {
 
 template <typename T, int EPI>
 hipError_t configure_epi() {
-  hipError_t e = configure_one<T, 256, 256, EPI, 8>();
-  if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 4>();
-  if (e == hipSuccess) e = configure_one<T, 64, 64, EPI, 4>();
+  hipError_t e = configure_one<T, 256, 256, EPI, 8, 2>();
+  if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 4, 4>();
+  if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 4, 2>();
+  if (e == hipSuccess) e = configure_one<T, 64, 64, EPI, 4, 4>();
   return e;
 }
 
@@ -499,7 +523,7 @@ const char* gemm_config_name(int dtype, int M, int N, int K) {
   (void)dtype; (void)K;
   const int c = pick_cfg(M, N);
   if (c == 2 && use_ksplit(M, N)) return "32x32 k-split";
-  return kCfgs[c].name;
+  return c == kCfg128TwoStage ? "128x128 (2 stages)" : kCfgs[c].name;
 }
 
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs& g, hipStream_t s) {
