@@ -51,6 +51,14 @@ def test_create_rejects_bad_arguments():
     assert L.slp_segment_create(None, 2, 0, 0, ctypes.byref(opts), ctypes.byref(h)) == -1
     # 2^20 x 2^20 weights cannot be addressed
     assert _create([1 << 20, 1 << 20])[0] == -2
+    # the limit itself: a weight matrix (its float32 master copy) must stay below 2 GiB (32-bit byte offsets)
+    assert _create([23176, 23176], dtype=api.BF16)[0] == -2
+    assert b"2 GiB" in L.slp_last_error()
+    for dt in (api.F32, api.BF16):
+        rc, h = _create([23168, 23168], dtype=dt)                     # 2,147,024,896 bytes: just below
+        assert rc == 0
+        L.slp_segment_destroy(h)
+    assert _create([16, 16], max_batch=1 << 27)[0] == -2              # an activation matrix of 8 GiB
 
 
 def test_sizes_and_state_errors_without_device():
