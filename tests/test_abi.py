@@ -58,7 +58,8 @@ def test_create_rejects_bad_arguments():
         rc, h = _create([23168, 23168], dtype=dt)                     # 2,147,024,896 bytes: just below
         assert rc == 0
         L.slp_segment_destroy(h)
-    assert _create([16, 16], max_batch=1 << 27)[0] == -2              # an activation matrix of 8 GiB
+    assert _create([16, 16], max_batch=(1 << 24) + 1)[0] == -1        # max_batch itself is capped at 2^24
+    assert _create([64, 64], max_batch=1 << 24)[0] == -2              # an activation matrix of 4 GiB
 
 
 def test_sizes_and_state_errors_without_device():
