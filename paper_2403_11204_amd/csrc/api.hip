@@ -220,9 +220,17 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
       HIP_TRY(hipEventRecord(seg->ev_fork[l - 1], st));
       HIP_TRY(hipStreamWaitEvent(us, seg->ev_fork[l - 1], 0));
     }
-    HIP_TRY(launch_bias_grad(seg->dtype, seg->dZT[l], seg->ldb, ly.N, batch, ly.db, us));
-    HIP_TRY(launch_sgd_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->lr, seg->mu, 0, us));
-    HIP_TRY(launch_bias_update(ly.b, ly.vb, ly.db, ly.N, seg->lr, seg->mu, us));
+    // small layers are bound by launch latency: weights and bias in one launch.  Large ones run the bias part as a launch
+    // of its own first: inside one launch its long reads of dZ^T slowed the matrix products beside it (measured 1 %).
+    if ((size_t)ly.N * ly.K <= ((size_t)1 << 22)) {
+      HIP_TRY(launch_layer_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->dZT[l],
+                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, us));
+    } else {
+      HIP_TRY(launch_layer_update(seg->dtype, nullptr, nullptr, nullptr, ly.N, 0, ly.ldk, nullptr, nullptr, ly.ldn, seg->dZT[l],
+                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, us));
+      HIP_TRY(launch_layer_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, nullptr, 0, 0,
+                                  nullptr, nullptr, nullptr, seg->lr, seg->mu, 0, us));
+    }
   }
   if (seg->L > 1) {     // join: later work on the caller's stream sees every update
     HIP_TRY(hipEventRecord(seg->ev_join, seg->side));
@@ -234,7 +242,8 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
 int refresh_copies(slp_segment* s, int layer, hipStream_t st) {
   Layer& ly = s->layers[layer];
   if (!ly.W16 && !ly.WT) return SLP_OK;
-  HIP_TRY(launch_sgd_update(s->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, 0.0f, 0.0f, 1, st));
+  HIP_TRY(launch_layer_update(s->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, nullptr, 0, 0, nullptr,
+                              nullptr, nullptr, 0.0f, 0.0f, 1, st));
   return SLP_OK;
 }
 

@@ -207,27 +207,30 @@ __global__ __launch_bounds__(256) void xent_loss_grad_kernel(const T* __restrict
                                                              T* __restrict__ dZ, float* __restrict__ row_loss) {
   const int lane = threadIdx.x & 63;
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (m >= B) return;
-  const T* z = ZL + (size_t)m * ld;
-  float mx = -INFINITY;
-  for (int c = lane; c < C; c += 64) mx = fmaxf(mx, to_f32(z[c]));
-  mx = wave_max(mx);
-  float sum = 0.0f;
-  for (int c = lane; c < C; c += 64) sum += expf(to_f32(z[c]) - mx);
-  sum = wave_sum(sum);
-  const float lse = mx + logf(sum);
-  const int cls = min(max(y[m], 0), C - 1);
-  if (lane == 0) row_loss[m] = lse - to_f32(z[cls]);
-  T* g = dZ + (size_t)m * ld;
-  for (int c = lane; c < C; c += 64) {
-    const float zc = to_f32(z[c]);
-    const float p = expf(zc - lse);
-    const float d = (p - (c == cls ? 1.0f : 0.0f)) * inv_b;
-    g[c] = from_f32<T>((relu_last && !(zc > 0.0f)) ? 0.0f : d);
+  if (m < B) {
+    const T* z = ZL + (size_t)m * ld;
+    float mx = -INFINITY;
+    for (int c = lane; c < C; c += 64) mx = fmaxf(mx, to_f32(z[c]));
+    mx = wave_max(mx);
+    float sum = 0.0f;
+    for (int c = lane; c < C; c += 64) sum += expf(to_f32(z[c]) - mx);
+    sum = wave_sum(sum);
+    const float lse = mx + logf(sum);
+    const int cls = min(max(y[m], 0), C - 1);
+    if (lane == 0) row_loss[m] = lse - to_f32(z[cls]);
+    T* g = dZ + (size_t)m * ld;
+    for (int c = lane; c < C; c += 64) {
+      const float zc = to_f32(z[c]);
+      const float p = expf(zc - lse);
+      const float d = (p - (c == cls ? 1.0f : 0.0f)) * inv_b;
+      g[c] = from_f32<T>((relu_last && !(zc > 0.0f)) ? 0.0f : d);
+    }
   }
 }
 
-// out = scale * sum(partials), summed in double in a fixed order by one block
+// out = scale * sum(partials), summed in double in a fixed order by one block.  (A separate launch on purpose:
+// finishing the sum inside the loss kernels -- last block counted in by an atomic -- needs a device-scope fence per
+// block, which on this chip writes back the whole L2 of the block's XCD: measured 25x slower than this launch.)
 __global__ __launch_bounds__(256) void reduce_loss_kernel(const float* __restrict__ partials, int n, double scale,
                                                           float* out0, float* out1) {
   __shared__ double red[256];
@@ -249,13 +252,15 @@ __global__ __launch_bounds__(256) void reduce_loss_kernel(const float* __restric
 // ---------------------------------------------------------------------------------
 // bias gradient: row sums of dZ^T, one wavefront per output feature
 // ---------------------------------------------------------------------------------
+// then the bias's own momentum update: v = mu v + db; b -= lr v (the gradient is kept for inspection)
 template <typename T>
-__global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dZT, int ldt, int N, int B,
-                                                        float* __restrict__ db) {
+__device__ __forceinline__ void bias_grad_update_block(int block, const T* __restrict__ dZT, int ldt, int N, int B,
+                                                       float* __restrict__ db, float* __restrict__ b,
+                                                       float* __restrict__ vb, float lr, float mu) {
   constexpr int V = 16 / sizeof(T);
   typedef T vec_t __attribute__((ext_vector_type(V)));
   const int lane = threadIdx.x & 63;
-  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int n = block * 4 + (threadIdx.x >> 6);
   if (n >= N) return;
   const T* row = dZT + (size_t)n * ldt;
   const int Bv = (B + V - 1) / V;      // pads up to the chunk boundary are zero
@@ -266,7 +271,15 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dZ
     for (int e = 0; e < V; ++e) acc += to_f32((T)v[e]);
   }
   acc = wave_sum(acc);
-  if (lane == 0) db[n] = acc;
+  if (lane == 0) {
+    db[n] = acc;
+    float v = acc;
+    if (mu != 0.0f) {
+      v = mu * vb[n] + v;
+      vb[n] = v;
+    }
+    b[n] -= lr * v;
+  }
 }
 
 // ---------------------------------------------------------------------------------
@@ -279,15 +292,15 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const T* __restrict__ dZ
 // zeros in all three streams and stay zero under the update, so the row direction needs
 // no tail handling.
 template <typename T>
-__global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32, float* __restrict__ vW,
-                                                         const float* __restrict__ dW, int N, int K, int ldk,
-                                                         bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
-                                                         float mu, int refresh_only) {
+__device__ __forceinline__ void sgd_update_block(int bx, int by, float* __restrict__ W32, float* __restrict__ vW,
+                                                 const float* __restrict__ dW, int N, int K, int ldk,
+                                                 bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
+                                                 float mu, int refresh_only) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   typedef T tx4 __attribute__((ext_vector_type(4)));
   typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
   __shared__ T tile[64][68];
-  const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
+  const int n0 = by * 64, k0 = bx * 64;
   const int q = threadIdx.x & 15, r = threadIdx.x >> 4;
   const int k = k0 + q * 4;
   // all loads of the thread's four rows are issued before the first store, so that 9 to 12
@@ -341,16 +354,31 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32
   }
 }
 
-__global__ void bias_update_kernel(float* __restrict__ b, float* __restrict__ vb, const float* __restrict__ db, int N,
-                                   float lr, float mu) {
-  const int n = blockIdx.x * blockDim.x + threadIdx.x;
-  if (n >= N) return;
-  float v = db[n];
-  if (mu != 0.0f) {
-    v = mu * vb[n] + v;
-    vb[n] = v;
-  }
-  b[n] -= lr * v;
+// One launch updates a whole layer: blocks [0, kb*nb) each own a 64x64 tile of the weight matrix, the blocks after
+// them 4 output features of the bias each (gradient = row sum of dZ^T, then the same momentum update).
+struct LayerUpdate {
+  float *W32, *vW; const float* dW; int N, K, ldk; void* W16; void* WT; int ldn;     // weights [N][ldk]
+  const void* dZT; int ldt, B; float *db, *b, *vb;                                     // bias: dZT [N][ldt]; null = weights only
+  float lr, mu; int refresh_only;
+};
+
+// the weight matrix alone, one block per 64x64 tile on a 2-D grid (large layers)
+template <typename T>
+__global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32, float* __restrict__ vW,
+                                                         const float* __restrict__ dW, int N, int K, int ldk,
+                                                         bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
+                                                         float mu, int refresh_only) {
+  sgd_update_block<T>(blockIdx.x, blockIdx.y, W32, vW, dW, N, K, ldk, W16, WT, ldn, lr, mu, refresh_only);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void layer_update_kernel(const LayerUpdate u) {
+  const int kb = (u.K + 63) / 64, nb = (u.N + 63) / 64;
+  const int id = blockIdx.x;
+  if (id < kb * nb)
+    sgd_update_block<T>(id % kb, id / kb, u.W32, u.vW, u.dW, u.N, u.K, u.ldk, (bf16*)u.W16, (T*)u.WT, u.ldn, u.lr, u.mu, u.refresh_only);
+  else
+    bias_grad_update_block<T>(id - kb * nb, (const T*)u.dZT, u.ldt, u.N, u.B, u.db, u.b, u.vb, u.lr, u.mu);
 }
 
 }  // namespace
@@ -413,25 +441,21 @@ hipError_t launch_reduce_loss(const float* partials, int n, double scale, float*
   return hipGetLastError();
 }
 
-hipError_t launch_bias_grad(int dtype, const void* dZT, int ldt, int N, int B, float* db, hipStream_t s) {
-  const int grid = (N + 3) / 4;
-  if (dtype == 1) bias_grad_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)dZT, ldt, N, B, db);
-  else bias_grad_kernel<float><<<grid, 256, 0, s>>>((const float*)dZT, ldt, N, B, db);
-  return hipGetLastError();
-}
-
-hipError_t launch_sgd_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16,
-                             void* WT, int ldn, float lr, float mu, int refresh_only, hipStream_t s) {
-  dim3 grid((K + 63) / 64, (N + 63) / 64);
-  if (dtype == 1)
-    sgd_update_kernel<bf16><<<grid, 256, 0, s>>>(W32, vW, dW, N, K, ldk, (bf16*)W16, (bf16*)WT, ldn, lr, mu, refresh_only);
-  else
-    sgd_update_kernel<float><<<grid, 256, 0, s>>>(W32, vW, dW, N, K, ldk, nullptr, (float*)WT, ldn, lr, mu, refresh_only);
-  return hipGetLastError();
-}
-
-hipError_t launch_bias_update(float* b, float* vb, const float* db, int N, float lr, float mu, hipStream_t s) {
-  bias_update_kernel<<<(N + 255) / 256, 256, 0, s>>>(b, vb, db, N, lr, mu);
+hipError_t launch_layer_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16, void* WT,
+                               int ldn, const void* dZT, int ldt, int B, float* db, float* b, float* vb, float lr, float mu,
+                               int refresh_only, hipStream_t s) {
+  if (!dZT) {       // weights only
+    dim3 grid2((K + 63) / 64, (N + 63) / 64);
+    if (dtype == 1)
+      sgd_update_kernel<bf16><<<grid2, 256, 0, s>>>(W32, vW, dW, N, K, ldk, (bf16*)W16, (bf16*)WT, ldn, lr, mu, refresh_only);
+    else
+      sgd_update_kernel<float><<<grid2, 256, 0, s>>>(W32, vW, dW, N, K, ldk, nullptr, (float*)WT, ldn, lr, mu, refresh_only);
+    return hipGetLastError();
+  }
+  const LayerUpdate u{W32, vW, dW, N, K, ldk, dtype == 1 ? W16 : nullptr, WT, ldn, dZT, ldt, B, db, b, vb, lr, mu, refresh_only};
+  const int grid = ((K + 63) / 64) * ((N + 63) / 64) + (dZT ? (N + 3) / 4 : 0);
+  if (dtype == 1) layer_update_kernel<bf16><<<grid, 256, 0, s>>>(u);
+  else layer_update_kernel<float><<<grid, 256, 0, s>>>(u);
   return hipGetLastError();
 }
 

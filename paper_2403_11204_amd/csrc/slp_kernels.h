@@ -60,15 +60,13 @@ hipError_t launch_xent_loss_grad(int dtype, const void* ZL, int ld, const int32_
 // out0[0] (and out1[0] if not null) = scale * sum(partials[0..n)), fixed summation order.
 hipError_t launch_reduce_loss(const float* partials, int n, double scale, float* out0, float* out1, hipStream_t s);
 
-// db[n] = sum_{m < B} dZT[n][m]
-hipError_t launch_bias_grad(int dtype, const void* dZT, int ldt, int N, int B, float* db, hipStream_t s);
-
-// SGD with momentum on one weight matrix: v = mu v + g; w -= lr v; then the derived
-// copies: W16 (bf16 [N][ldk], bf16 mode only) and WT ([K][ldn], element type T, optional).
-// refresh_only: skip the arithmetic and only rebuild the copies from W32.
-hipError_t launch_sgd_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16,
-                             void* WT, int ldn, float lr, float mu, int refresh_only, hipStream_t s);
-hipError_t launch_bias_update(float* b, float* vb, const float* db, int N, float lr, float mu, hipStream_t s);
+// One launch per layer: SGD with momentum on the weight matrix (v = mu v + g; w -= lr v), its derived copies
+// W16 (bf16 [N][ldk], bf16 mode only) and WT ([K][ldn], element type T, optional), and -- unless dZT is null --
+// the bias: db[n] = sum_{m < B} dZT[n][m], then the same update on b, vb.
+// refresh_only: skip the arithmetic and only rebuild the copies from W32 (dZT must be null).
+hipError_t launch_layer_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16, void* WT,
+                               int ldn, const void* dZT, int ldt, int B, float* db, float* b, float* vb, float lr, float mu,
+                               int refresh_only, hipStream_t s);
 
 // Counter-based generators (Philox4x32-10).
 hipError_t launch_make_labels(uint64_t seed, int classes, int dim, int dist, float kappa, void* out, int dt,
