@@ -16,7 +16,13 @@
  *     parameter count (in+1)*out (Sec. 3);
  *   - a label table is stored [classes][dim]: row j is the synthetic intermediate
  *     label of class j (the paper's SIL is the transpose, one column per class).
- *   - argument validation happens on the host before any device work is queued.
+ *   - argument validation happens on the host before any device work is queued: a call
+ *     that returns an error has launched nothing;
+ *   - calls on ONE handle must not overlap in time (they share its workspace); different
+ *     handles are independent and may run concurrently on different streams (Sec. 2.1:
+ *     partitions are independent jobs).  A training step also uses a second stream that
+ *     the handle owns (default priority) for parameter updates; it is forked from and
+ *     joined back into `stream` inside the call, so `stream` alone orders everything.
  */
 #ifndef SLP_H
 #define SLP_H
@@ -87,7 +93,11 @@ int slp_make_segment_inputs(uint64_t seed, const float* table /*device*/, int cl
 
 /* ---- segment handle (Sec. 2: one partition; Sec. 2.1: its own hyper-parameters) ----
  * widths[0..n_widths-1] = input width then the width of every layer, n_widths >= 2.
- * The handle is host memory owned by the library until slp_segment_destroy. */
+ * The handle is host memory owned by the library until slp_segment_destroy.
+ * Errors: SLP_ERR_ARG (null pointers, n_widths < 2, a width <= 0, unknown enum, max_batch
+ * outside [1, 2^24], lr < 0, momentum outside [0,1)); SLP_ERR_SHAPE when a matrix cannot be
+ * addressed with 32-bit byte offsets: a weight matrix (float32, leading dimension rounded up
+ * to 8) or an activation matrix (max_batch x width in the handle's dtype) of 2 GiB or more. */
 int slp_segment_create(const int* widths /*host*/, int n_widths, int act, int loss, const slp_opts* opts /*host*/,
                        slp_segment** out);
 void slp_segment_destroy(slp_segment* seg);
@@ -99,7 +109,9 @@ size_t slp_segment_workspace_bytes(const slp_segment* seg);
 
 /* Hands the two caller-owned device buffers (256-byte aligned, at least the sizes
  * above) to the segment and zero-fills them on `stream`.  They must outlive every
- * later call on the handle; the library never frees them. */
+ * later call on the handle; the library never frees them.  Parameters are undefined
+ * (zero) until slp_segment_init or slp_segment_set_params on every layer.
+ * Errors: SLP_ERR_ARG (null), SLP_ERR_ALLOC (misaligned or too small), SLP_ERR_DEVICE. */
 int slp_segment_bind(slp_segment* seg, void* params /*device*/, size_t params_bytes, void* workspace /*device*/,
                      size_t workspace_bytes, slp_stream stream);
 
@@ -112,7 +124,9 @@ int slp_segment_init(slp_segment* seg, uint64_t seed, slp_stream stream);
  * b[out] whatever the internal layout; layer in [0, n_widths-2]; on_device selects
  * host or device pointers for W and b; either pointer may be NULL to skip it.  The
  * calls synchronise `stream` before returning when a host pointer is involved.
- * set_params also rebuilds the derived weight copies and leaves momentum alone. */
+ * set_params also rebuilds the derived weight copies and leaves momentum alone.
+ * Errors: SLP_ERR_ARG (layer out of range), SLP_ERR_STATE (not bound; get_* before any
+ * parameters exist), SLP_ERR_DEVICE. */
 int slp_segment_set_params(slp_segment* seg, int layer, const float* W, const float* b, int on_device, slp_stream stream);
 int slp_segment_get_params(slp_segment* seg, int layer, float* W, float* b, int on_device, slp_stream stream);
 int slp_segment_get_grads(slp_segment* seg, int layer, float* dW, float* db, int on_device, slp_stream stream);
@@ -125,7 +139,9 @@ int slp_segment_get_activation(slp_segment* seg, int layer, int kind, int batch,
 int slp_segment_set_lr(slp_segment* seg, float lr, float momentum);
 
 /* Label table for a SLP_MSE_SIL segment: float32 [classes][dim] on the device with
- * dim == the segment's last width; caller-owned, must outlive the steps. */
+ * dim == the segment's last width; caller-owned, must outlive the steps.
+ * Errors: SLP_ERR_STATE (the segment's loss is not SLP_MSE_SIL), SLP_ERR_ARG (null table,
+ * classes <= 0), SLP_ERR_SHAPE (dim != last width). */
 int slp_segment_set_labels(slp_segment* seg, const float* table /*device*/, int classes, int dim);
 
 /* ---- the training step (Sec. 2: first and second training phase; Sec. 3:
@@ -136,13 +152,17 @@ int slp_segment_set_labels(slp_segment* seg, const float* table /*device*/, int 
  * label table; for SLP_SOFTMAX_XENT they are the classes (< last width).  Ids are
  * clamped into range on the device.  If loss_out is not NULL the mean loss of the
  * batch (before the update) is written there (float32, device).  No host
- * synchronisation; X and targets are only read. */
+ * synchronisation; X and targets are only read.  batch may be any value in
+ * [1, max_batch]; the means run over the batch actually passed.
+ * Errors: SLP_ERR_ARG (null X or targets), SLP_ERR_SHAPE (batch outside [1, max_batch]),
+ * SLP_ERR_STATE (not bound, no parameters, SLP_MSE_SIL without a label table),
+ * SLP_ERR_DEVICE (a launch failed). */
 int slp_segment_step(slp_segment* seg, const void* X /*device*/, const int32_t* targets /*device*/, int batch,
                      float* loss_out /*device, may be NULL*/, slp_stream stream);
 
 /* Forward only (Sec. 2: the stored response of the left partition; joining the
  * partitions): out[batch][last width], dense, handle dtype, device.  Parameters
- * are not changed; the activation workspace is overwritten. */
+ * are not changed; the activation workspace is overwritten.  Errors as for the step. */
 int slp_segment_forward(slp_segment* seg, const void* X /*device*/, int batch, void* out /*device*/, slp_stream stream);
 
 /* ---- recovery phase (Sec. 5: the left partition is trained some more while the
