@@ -94,7 +94,7 @@ int slp_make_segment_inputs(uint64_t seed, const float* table /*device*/, int cl
 /* ---- segment handle (Sec. 2: one partition; Sec. 2.1: its own hyper-parameters) ----
  * widths[0..n_widths-1] = input width then the width of every layer, n_widths >= 2.
  * The handle is host memory owned by the library until slp_segment_destroy.
- * Errors: SLP_ERR_ARG (null pointers, n_widths < 2, a width <= 0, unknown enum, max_batch
+ * Errors: SLP_ERR_ARG (null pointers, n_widths < 2 or > 65, a width outside [1, 2^20], unknown enum, max_batch
  * outside [1, 2^24], lr < 0, momentum outside [0,1)); SLP_ERR_SHAPE when a matrix cannot be
  * addressed with 32-bit byte offsets: a weight matrix (float32, leading dimension rounded up
  * to 8) or an activation matrix (max_batch x width in the handle's dtype) of 2 GiB or more. */
