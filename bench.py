@@ -58,6 +58,10 @@ CONFIGS = {
             lr=0.01, mom=0.9, streams=False,
             segs=[([784, 16384, 16384, 16384], ALL, MSE, api.UNIFORM_PM1, 31),
                   ([16384, 16384, 16384, 1000], LAST, CE, None, None)]),
+    # the network of the paper's own experiment (Sec. 3): 784-80-60 | 60-60-60-47, batch 1410, labels 10 * U(0,1)
+    5: dict(name="paper Sec. 3 network 784-80-60 | 60-60-60-47 fp32", dtype=api.F32, batch=1410, classes=47, lr=0.01, mom=0.9,
+            streams=False, graph=True, kappa=10.0,
+            segs=[([784, 80, 60], ALL, MSE, api.UNIFORM01, 3), ([60, 60, 60, 47], LAST, CE, None, None)]),
 }
 E2E_WIDTHS = [784, 16384, 16384, 16384, 16384, 16384, 1000]
 
@@ -88,7 +92,7 @@ def build_segments(cfg, n_batches):
         else:   # an interior/final segment sees the previous cut's label of the class plus noise (sigma 0.05)
             inputs.append([api.make_segment_inputs(5 + si, prev_table, ys[i], i * B, 0.05, dt) for i in range(n_batches)])
         if loss == MSE:
-            prev_table = api.make_synthetic_labels(seed, classes, widths[-1], dist, 1.0, api.F32)
+            prev_table = api.make_synthetic_labels(seed, classes, widths[-1], dist, cfg.get("kappa", 1.0), api.F32)
             seg.set_labels(prev_table)
         segs.append(seg)
     return segs, inputs, ys
@@ -156,7 +160,7 @@ def cpu_baseline(cfg, rows, max_seconds=60.0):
         xin = X if si == 0 else orng.make_segment_inputs(5 + si, prev, y, 0, 0.05)
         table = None
         if loss == MSE:
-            table = orng.make_synthetic_labels(seed, classes, widths[-1], dist, 1.0)
+            table = orng.make_synthetic_labels(seed, classes, widths[-1], dist, cfg.get("kappa", 1.0))
             prev = table
         t0 = time.perf_counter()
         o.step(xin, y, table)
@@ -187,7 +191,7 @@ def main():
     cfg = dict(CONFIGS[args.config])
     if args.serial:
         cfg["streams"] = False
-    big = args.config >= 3
+    big = args.config in (3, 4)
     steps = args.steps if args.steps is not None else (20 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
     dt, B = cfg["dtype"], cfg["batch"]
@@ -268,7 +272,7 @@ def main():
         torch.cuda.empty_cache()
 
     if not args.no_cpu:
-        rows = args.cpu_rows or {0: 64, 1: 256, 2: 256, 3: 16, 4: 8}[args.config]
+        rows = args.cpu_rows or {0: 64, 1: 256, 2: 256, 3: 16, 4: 8, 5: 1410}[args.config]
         out["cpu_baseline"] = cpu_baseline(cfg, rows)
     print(json.dumps(out), flush=True)
 
