@@ -17,7 +17,8 @@
 //     wavefronts (128x64 each, 128 accumulator registers, two wavefronts per SIMD so that one
 //     can issue MFMAs while the other waits on LDS or the barrier): measured 4 % faster than
 //     4 wavefronts of 128x128 in spite of 50 % more LDS reads, and its epilogues do not spill.
-//     The 128x128 and 64x64 tiles run with 4 wavefronts.
+//     The 64x64 tile runs with 4 wavefronts; the 128x128 tile with 8 (64x32 each) in its four-stage
+//     form and with 4 (64x64 each) in its two-stage form, where two workgroups share a compute unit.
 //   * bf16: v_mfma_f32_32x32x16_bf16, one per 16-byte chunk pair; float32:
 //     v_mfma_f32_32x32x2_f32, four per 16-byte chunk pair.  A k-tile is 128 bytes
 //     per row for both types (64 bf16 / 32 float), so loads, LDS layout and
@@ -461,7 +462,7 @@ template <typename T, int EPI>
 hipError_t launch_cfg(int cfg, const GemmArgs& g, hipStream_t s) {
   switch (cfg) {
     case 0: return launch_one<T, 256, 256, EPI, 8, 2>(g, s);
-    case 1: return launch_one<T, 128, 128, EPI, 4, 4>(g, s);
+    case 1: return launch_one<T, 128, 128, EPI, 8, 4>(g, s);     // 8 wavefronts of 64x32: +5-10 % over 4 of 64x64 here
     case kCfg128TwoStage: return launch_one<T, 128, 128, EPI, 4, 2>(g, s);
     default: return launch_one<T, 64, 64, EPI, 4, 4>(g, s);
   }
@@ -499,7 +500,7 @@ hipError_t launch_epi(int epi, int cfg, const GemmArgs& g, hipStream_t s) {
 template <typename T, int EPI>
 hipError_t configure_epi() {
   hipError_t e = configure_one<T, 256, 256, EPI, 8, 2>();
-  if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 4, 4>();
+  if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 8, 4>();
   if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 4, 2>();
   if (e == hipSuccess) e = configure_one<T, 64, 64, EPI, 4, 4>();
   return e;
