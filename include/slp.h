@@ -193,7 +193,10 @@ int slp_segment_step_external(slp_segment* seg, const void* X /*device*/, const 
  * null stream, for the first step of a handle, and when `stream` is already being captured by
  * the caller (the launches then become part of the caller's graph).  slp_segment_set_lr,
  * slp_segment_set_labels and slp_segment_bind drop the captured graphs (after a device
- * synchronisation), because those hold their values.  Off by default. */
+ * synchronisation), because those hold their values.  A caller that keeps passing new
+ * combinations would pay a capture per step: after 32 misses in a row the handle returns to
+ * eager launches until this function is called again (copy each batch into one fixed buffer
+ * and step on that to have a single combination).  Off by default. */
 int slp_segment_set_graph(slp_segment* seg, int on);
 
 /* ---- measurement hooks -------------------------------------------------------------

@@ -94,6 +94,7 @@ struct slp_segment {
   // Small segments are bound by launch latency, not by the GPU: with graphs on, the launch sequence of a step
   // is captured once per (X, targets, batch, loss_out) and replayed as one graph launch afterwards.
   bool use_graph, graph_warm;
+  int graph_misses;                          // consecutive steps that found no captured graph
   std::vector<StepGraph> graphs;
   uint64_t graph_tick;
 };
@@ -377,7 +378,7 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
 
   s->side = nullptr; s->ev_join = nullptr;
   s->bound = false; s->have_params = false; s->table = nullptr; s->classes = 0; s->last_batch = 0; s->prof = false;
-  s->use_graph = false; s->graph_warm = false; s->graph_tick = 0;
+  s->use_graph = false; s->graph_warm = false; s->graph_tick = 0; s->graph_misses = 0;
   s->partials = nullptr; s->loss_dev = nullptr;
   *out = s;
   return SLP_OK;
@@ -551,7 +552,11 @@ int slp_segment_step(slp_segment* seg, const void* X, const int32_t* targets, in
   // before anything is captured.
   hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
   if (seg->use_graph && st) HIP_TRY(hipStreamIsCapturing(st, &cap));
-  if (!seg->use_graph || seg->prof || !st || cap != hipStreamCaptureStatusNone || !seg->graph_warm) {
+  // A caller that never repeats a combination (a loop over more distinct batch buffers than the cache holds) would
+  // pay a capture per step: after 2 x cache size misses in a row the handle goes back to eager launches until
+  // slp_segment_set_graph is called again.
+  const bool thrashing = seg->graph_misses > 2 * (int)kMaxStepGraphs;
+  if (!seg->use_graph || thrashing || seg->prof || !st || cap != hipStreamCaptureStatusNone || !seg->graph_warm) {
     seg->graph_warm = true;
     return launch_all();
   }
@@ -559,9 +564,11 @@ int slp_segment_step(slp_segment* seg, const void* X, const int32_t* targets, in
   for (auto& g : seg->graphs)
     if (g.X == X && g.targets == targets && g.batch == batch && g.loss_out == loss_out) {
       g.used = seg->graph_tick;
+      seg->graph_misses = 0;
       HIP_TRY(hipGraphLaunch(g.exec, st));
       return SLP_OK;
     }
+  ++seg->graph_misses;
   HIP_TRY(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
   rc = launch_all();
   hipGraph_t graph = nullptr;
@@ -593,6 +600,7 @@ int slp_segment_set_graph(slp_segment* seg, int on) {
   if (rc) return rc;
   if (on) HIP_TRY(gemm_configure_all());
   seg->use_graph = on != 0;
+  seg->graph_misses = 0;
   if (!seg->use_graph) drop_graphs(seg);
   return SLP_OK;
 }

@@ -26,13 +26,24 @@ def _batches(n, batch):
         yield s, min(s + batch, n)
 
 
-def train_epochs(seg, X, y, epochs, batch):
-    """Consecutive, unshuffled batches for `epochs` passes.  Returns the mean loss of each epoch."""
+def train_epochs(seg, X, y, epochs, batch, staged=False):
+    """Consecutive, unshuffled batches for `epochs` passes.  Returns the mean loss of each epoch.
+
+    staged: copy every batch into one fixed pair of buffers and step on those, so that a handle with graph
+    replay on (Segment.set_graph) sees a single argument combination per batch size and replays one graph."""
     n = X.shape[0]
     losses = torch.zeros((epochs, (n + batch - 1) // batch), dtype=torch.float32, device=X.device)
+    if staged:
+        Xs = torch.empty((batch, X.shape[1]), dtype=X.dtype, device=X.device)
+        ys = torch.empty(batch, dtype=y.dtype, device=y.device)
     for ep in range(epochs):
         for i, (a, b) in enumerate(_batches(n, batch)):
-            losses[ep, i] = seg.step(X[a:b], y[a:b])[0]
+            if staged:
+                Xs[:b - a].copy_(X[a:b])
+                ys[:b - a].copy_(y[a:b])
+                losses[ep, i] = seg.step(Xs[:b - a], ys[:b - a])[0]
+            else:
+                losses[ep, i] = seg.step(X[a:b], y[a:b])[0]
     return losses.mean(dim=1).tolist()
 
 

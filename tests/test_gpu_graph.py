@@ -108,3 +108,28 @@ def test_graph_on_the_null_stream_falls_back_to_eager_launches():
         assert torch.equal(le, lg)
     assert same_state(eager, graph)
     assert np.isfinite(float(le))
+
+
+def test_staged_epochs_replay_one_graph_and_match_eager_epochs():
+    from paper_2403_11204_amd import pipeline
+    B, classes, n = 64, 7, 64 * 40 + 23            # 40 full batches (more than the cache holds) and a ragged one
+    eager, graph = twin([30, 50, 20], api.RELU_ALL, api.MSE_SIL, api.F32, B, wseed=11)
+    table = api.make_synthetic_labels(5, classes, 20, api.UNIFORM_PM1)
+    for s in (eager, graph):
+        s.set_labels(table)
+    graph.set_graph(True)
+    X, y = datagen.class_mean_inputs(n, classes, dim=30, seed=6)
+    Xd, yd = torch.from_numpy(X).to(DEV).contiguous(), torch.from_numpy(y).to(DEV)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        le = pipeline.train_epochs(eager, Xd, yd, epochs=2, batch=B)
+        lg = pipeline.train_epochs(graph, Xd, yd, epochs=2, batch=B, staged=True)
+        assert le == lg
+        assert same_state(eager, graph)
+        # unstaged with graphs on: every batch is a new combination; the handle must fall back to eager launches
+        le = pipeline.train_epochs(eager, Xd, yd, epochs=1, batch=B)
+        lg = pipeline.train_epochs(graph, Xd, yd, epochs=1, batch=B)
+        assert le == lg
+        assert same_state(eager, graph)
+    torch.cuda.synchronize()
