@@ -111,3 +111,37 @@ def test_free_functions_reject_bad_arguments():
     assert L.slp_probe_mfma_rate(1, 0, dummy, 1 << 22, ctypes.byref(tf), None, None) == -1
     assert L.slp_probe_mfma_rate(1, 10, None, 1 << 22, ctypes.byref(tf), None, None) == -1
     assert L.slp_probe_mfma_rate(1, 10, dummy, 1 << 22, None, None, None) == -1
+
+
+def test_header_is_plain_c(tmp_path):
+    # the boundary is C: the header must compile as C99 on its own, and a C caller must link against the library
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_slp.c"
+    src.write_text(
+        '#include "slp.h"\n'
+        '#include <stdio.h>\n'
+        'int main(void) {\n'
+        '  int widths[3] = {784, 80, 60};\n'
+        '  slp_opts o = {SLP_F32, 1410, 0.01f, 0.9f, 0};\n'
+        '  slp_segment* seg = NULL;\n'
+        '  int rc = slp_segment_create(widths, 3, SLP_RELU_ALL, SLP_MSE_SIL, &o, &seg);\n'
+        '  if (rc != SLP_OK) { printf("create failed: %s\\n", slp_last_error()); return 1; }\n'
+        '  printf("%zu %zu\\n", slp_segment_param_bytes(seg), slp_segment_workspace_bytes(seg));\n'
+        '  rc = slp_segment_step(seg, NULL, NULL, 8, NULL, NULL);   /* not bound, null X: an error code, no crash */\n'
+        '  slp_segment_destroy(seg);\n'
+        '  return rc < 0 ? 0 : 2;\n'
+        '}\n')
+    exe = tmp_path / "use_slp"
+    libdir = os.path.join(ROOT, "paper_2403_11204_amd")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe), "-L", libdir, "-l:libslp.so", "-Wl,-rpath," + libdir,
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    api_bytes = api.lib().slp_segment_param_bytes  # the same sizes through ctypes
+    rc, h = _create([784, 80, 60], max_batch=1410)
+    assert rc == 0 and int(out[0]) == api_bytes(h) and int(out[1]) == api.lib().slp_segment_workspace_bytes(h)
+    api.lib().slp_segment_destroy(h)
