@@ -1,4 +1,4 @@
-// Internal launch interface between the C ABI (api.cpp) and the HIP kernels.
+// Internal launch interface between the C ABI (api.hip) and the HIP kernels.
 // Not part of the public boundary; see include/slp.h for that.
 #pragma once
 
