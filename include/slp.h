@@ -162,7 +162,9 @@ int slp_segment_step(slp_segment* seg, const void* X /*device*/, const int32_t* 
 
 /* Forward only (Sec. 2: the stored response of the left partition; joining the
  * partitions): out[batch][last width], dense, handle dtype, device.  Parameters
- * are not changed; the activation workspace is overwritten.  Errors as for the step. */
+ * are not changed; the activation workspace is overwritten (X and out themselves are
+ * used in place of its first and last entries when their rows start on 16-byte
+ * boundaries: width a multiple of 8, pointer 16-byte aligned).  Errors as for the step. */
 int slp_segment_forward(slp_segment* seg, const void* X /*device*/, int batch, void* out /*device*/, slp_stream stream);
 
 /* ---- recovery phase (Sec. 5: the left partition is trained some more while the

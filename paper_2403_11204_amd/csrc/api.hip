@@ -153,14 +153,19 @@ int ingest(slp_segment* s, const void* X, int batch, bool with_transpose, hipStr
   return SLP_OK;
 }
 
-int forward_layers(slp_segment* s, int batch, bool training, hipStream_t st) {
+// x_direct / out_direct (forward-only passes): the caller's dense input is the first layer's operand and the caller's
+// dense output buffer the last layer's result, when their rows are 16-byte aligned; the workspace copies are skipped.
+int forward_layers(slp_segment* s, int batch, bool training, hipStream_t st, const void* x_direct = nullptr,
+                   void* out_direct = nullptr) {
   for (int l = 1; l <= s->L; ++l) {
     const Layer& ly = s->layers[l - 1];
     GemmArgs g{};
     g.A = s->A[l - 1]; g.lda = s->ldw[l - 1];
+    if (l == 1 && x_direct) { g.A = x_direct; g.lda = s->widths[0]; }
     g.B = ly.Wop;      g.ldb = ly.ldk;
     g.M = batch; g.N = ly.N; g.K = ly.K;
     g.C = s->A[l]; g.ldc = s->ldw[l];
+    if (l == s->L && out_direct) { g.C = out_direct; g.ldc = s->widths[l]; }
     g.CT = (training && l < s->L) ? s->AT[l] : nullptr; g.ldct = s->ldb;
     g.bias = ly.b; g.relu = relu_on(s, l) ? 1 : 0;
     int rc = run_gemm(s, EPI_FWD, g, st);
@@ -520,12 +525,19 @@ int slp_segment_forward(slp_segment* seg, const void* X, int batch, void* out, s
   if (!X || !out) return fail(SLP_ERR_ARG, "X and out must not be NULL");
   if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
   hipStream_t st = (hipStream_t)stream;
-  rc = ingest(seg, X, batch, false, st);
+  // the stored-response pass over a whole dataset (Sec. 2) is this call in a loop: no activation is kept for a
+  // backward pass, and dense caller buffers whose rows start on 16-byte boundaries are used in place
+  const int w0 = seg->widths[0], w = seg->widths[seg->L];
+  const bool x_direct = w0 % kLdAlign == 0 && ((uintptr_t)X & 15) == 0;
+  const bool out_direct = w % kLdAlign == 0 && ((uintptr_t)out & 15) == 0;
+  if (!x_direct) {
+    rc = ingest(seg, X, batch, false, st);
+    if (rc) return rc;
+  }
+  rc = forward_layers(seg, batch, false, st, x_direct ? X : nullptr, out_direct ? out : nullptr);
   if (rc) return rc;
-  rc = forward_layers(seg, batch, false, st);
-  if (rc) return rc;
-  const int w = seg->widths[seg->L];
-  HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[seg->L], seg->ldw[seg->L], batch, w, out, w, nullptr, 0, 0, nullptr, 0, st));
+  if (!out_direct)
+    HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[seg->L], seg->ldw[seg->L], batch, w, out, w, nullptr, 0, 0, nullptr, 0, st));
   seg->last_batch = batch;
   return SLP_OK;
 }
