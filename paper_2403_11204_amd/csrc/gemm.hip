@@ -41,6 +41,10 @@
 //     8.0 cycles per wavefront read for the naive (row & 7) swizzle).  The hardware writes
 //     lane l of an LDS-direct load at base + 16 l, so the swizzle is applied on the global
 //     side: each lane fetches the chunk that belongs at its physical position.
+//   * epilogue: a lane holds 4 consecutive rows of one output column per accumulator register quad, which
+//     is one vector store into the transposed output; for the row-major output the quad of lanes holding
+//     4 adjacent columns transposes its 4x4 block with DPP moves, after which a lane holds 4 consecutive
+//     columns of one row: one vector store as well (2 stores per quad instead of 5).
 //   * workgroup -> tile: consecutive workgroup ids go round-robin over the 8 XCDs, so
 //     ids are first regrouped per XCD (each XCD gets a contiguous range of tiles and
 //     its own 4 MB L2 sees a compact set of operand rows: measured L2 hit rate 79%), then
