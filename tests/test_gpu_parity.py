@@ -310,3 +310,44 @@ def test_mfma_probe_reports_a_rate_below_the_published_peak():
         small = torch.empty(16, device=DEV)
         api._check(api.lib().slp_probe_mfma_rate(api.BF16, 10, api._ptr(small), 64, ctypes.byref(tf), None, None))
     assert e.value.code == -2
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_shapes(seed):
+    # layer counts, widths and batch sizes drawn at random (seeded) around the chunk, tile and wavefront
+    # boundaries: odd widths, widths of 1, batches that end inside a chunk, every loss / activation / dtype
+    r = np.random.default_rng(1000 + seed)
+    L = int(r.integers(1, 4))
+    pool = [1, 2, 3, 7, 8, 9, 15, 16, 17, 31, 32, 33, 47, 63, 64, 65, 100, 127, 128, 129, 200, 255, 256, 257, 300]
+    widths = [int(r.choice(pool)) for _ in range(L + 1)]
+    B = int(r.choice([1, 2, 5, 8, 31, 32, 33, 64, 100, 129, 257, 300]))
+    dtype = api.BF16 if seed % 2 else api.F32
+    if r.integers(0, 2):
+        act, loss, classes = api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, widths[-1]
+        dist = None
+    else:
+        act, loss, classes = (api.RELU_ALL if r.integers(0, 2) else api.RELU_HIDDEN_IDENTITY_LAST), api.MSE_SIL, int(r.integers(1, 20))
+        dist = int(r.choice([api.UNIFORM01, api.UNIFORM_PM1, api.NORMAL, api.BINARY_PM1]))
+    mom = 0.9 if r.integers(0, 2) else 0.0
+    X, y, table = case_data(widths, loss, B, dist, classes, seed=seed + 3)
+    g, o = make_pair(widths, act, loss, dtype, max_batch=B + int(r.integers(0, 9)), lr=0.05, mom=mom, wseed=seed)
+    print("shape", widths, "batch", B, "dtype", dtype, "loss", loss, "act", act, flush=True)
+    check_step(g, o, X, y, table, dtype, steps=2)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_seeded_random_mid_size_shapes(seed):
+    # ragged sizes large enough to reach the 64x64, 128x128 (both forms) and 256x256 tile instantiations
+    r = np.random.default_rng(2000 + seed)
+    pool = [520, 777, 1000, 1234, 1999, 2500, 3100]
+    widths = [int(r.choice(pool)) for _ in range(3)]
+    B = int(r.choice([1000, 1500, 2100, 4100]))
+    dtype = api.BF16 if seed % 2 else api.F32
+    if seed % 3 == 0:
+        act, loss, classes, dist = api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, widths[-1], None
+    else:
+        act, loss, classes, dist = api.RELU_ALL, api.MSE_SIL, 33, api.NORMAL
+    X, y, table = case_data(widths, loss, B, dist, classes, seed=seed + 5)
+    g, o = make_pair(widths, act, loss, dtype, max_batch=B, lr=0.05, mom=0.9, wseed=seed + 40)
+    print("shape", widths, "batch", B, "dtype", dtype, "loss", loss, flush=True)
+    check_step(g, o, X, y, table, dtype)
