@@ -12,7 +12,9 @@ of paper Sec. 2 describe:
   phase 2   the right partition is trained for N_R epochs on (stored response, class);
   recovery  (Sec. 5) the left partition is trained further through the frozen right
             partition;
-  join      the partitions are chained for inference.
+  join      the partitions are chained for inference;
+  simultaneous  every partition trained at once, interior partitions on (synthetic
+            label of the previous cut + noise, own target).
 
 With more than two partitions, partition k is trained on the stored response of
 partition k-1 against its own label table (Sec. 2, the multi-partition variant).
@@ -79,6 +81,32 @@ def recovery_epochs(left, right, X, y, epochs, batch):
             losses[ep, i] = loss[0]
             left.step_external(X[a:b], d_resp)
     return losses.mean(dim=1).tolist()
+
+
+def train_simultaneous(segments, tables, X, y, epochs, batch, noise_seed=5, sigma=0.05):
+    """The variant that trains every partition at once (end of Sec. 2): partition 0 sees the data, partition k > 0
+    sees the synthetic label of the sample's class at cut k-1 plus noise (standard deviation sigma, counter = global
+    sample index, seed noise_seed + k) instead of the response of partition k-1, so no partition waits for another.
+    tables[k] is the float32 label table of cut k (already bound to segments[k] as its target).  Each partition
+    steps on a stream of its own.  Returns the mean loss of each epoch, per partition."""
+    from . import api
+    n = X.shape[0]
+    nb = (n + batch - 1) // batch
+    losses = [torch.zeros((epochs, nb), dtype=torch.float32, device=X.device) for _ in segments]
+    streams = [torch.cuda.Stream() for _ in segments]
+    cur = torch.cuda.current_stream()
+    for st in streams:
+        st.wait_stream(cur)
+    for ep in range(epochs):
+        for i, (a, b) in enumerate(_batches(n, batch)):
+            for k, (seg, st) in enumerate(zip(segments, streams)):
+                with torch.cuda.stream(st):
+                    xin = X[a:b] if k == 0 else api.make_segment_inputs(noise_seed + k, tables[k - 1], y[a:b], a, sigma, seg.dtype)
+                    losses[k][ep, i] = seg.step(xin, y[a:b])[0]
+                    xin.record_stream(st)
+    for st in streams:
+        cur.wait_stream(st)
+    return [l.mean(dim=1).tolist() for l in losses]
 
 
 def joined_forward(segments, X, batch):

@@ -148,3 +148,39 @@ def test_segments_stepping_concurrently_on_separate_streams():
         for l in range(a.L):
             (Wa, ba), (Wb, bb) = a.get_params(l), b.get_params(l)
             assert torch.equal(Wa, Wb) and torch.equal(ba, bb)
+
+
+def test_simultaneous_training_of_three_partitions_against_the_oracle():
+    # end of Sec. 2: every partition trained at once; interior partitions take the previous cut's label of the
+    # class plus noise as input.  Float32, 3 partitions, 2 epochs of 5 batches (the last one ragged).
+    n, B, classes = 300, 64, 6
+    specs = [([40, 56, 24], api.RELU_ALL, api.MSE_SIL), ([24, 48, 16], api.RELU_ALL, api.MSE_SIL),
+             ([16, 32, classes], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT)]
+    X, y = datagen.class_mean_inputs(n, classes, dim=40, seed=4)
+    tabs = [orng.make_synthetic_labels(60, classes, 24, orng.UNIFORM_PM1), orng.make_synthetic_labels(61, classes, 16, orng.NORMAL)]
+    gs, os_ = [], []
+    for k, (w, act, loss) in enumerate(specs):
+        g, o = pair(w, act, loss, api.F32, B, 0.05, 0.9, wseed=30 + k)
+        if loss == api.MSE_SIL:
+            g.set_labels(torch.from_numpy(tabs[k]).to(DEV))
+        gs.append(g)
+        os_.append(o)
+    Xd, yd = torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV)
+    dev_tabs = [torch.from_numpy(t).to(DEV) for t in tabs]
+    got = pipeline.train_simultaneous(gs, dev_tabs, Xd, yd, epochs=2, batch=B, noise_seed=5, sigma=0.05)
+    ref = [[], [], []]
+    Xv = X.astype(np.float64)
+    for ep in range(2):
+        per = [[], [], []]
+        for a in range(0, n, B):
+            b = min(a + B, n)
+            for k, o in enumerate(os_):
+                xin = Xv[a:b] if k == 0 else orng.make_segment_inputs(5 + k, tabs[k - 1], y[a:b], a, 0.05).astype(np.float64)
+                per[k].append(o.step(xin, y[a:b], tabs[k] if k < 2 else None)["loss"])
+        for k in range(3):
+            ref[k].append(float(np.mean(per[k])))
+    for k in range(3):
+        assert np.allclose(got[k], ref[k], rtol=1e-4), (k, got[k], ref[k])
+        assert got[k][1] < got[k][0]                                   # every partition learns
+        for l in range(2):
+            assert rel_err(to_np(gs[k].get_params(l)[0]), os_[k].W[l]) <= 1e-4
