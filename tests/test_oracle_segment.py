@@ -294,6 +294,31 @@ def test_loss_decreases_on_separable_toy_set():
     assert (pred == y).mean() > 0.95
 
 
+def test_simultaneous_variant_on_separable_toy_set():
+    # end of Sec. 2: the right partition never sees the left one's response while training -- its inputs are the
+    # synthetic label of the sample's class plus noise -- and the two still work when joined afterwards
+    g = np.random.default_rng(13)
+    centres = np.array([[0.1, 0.1, 0.9, 0.1], [0.9, 0.1, 0.1, 0.5], [0.1, 0.9, 0.5, 0.9]])
+    y = datagen.balanced_classes(96, 3)
+    X = np.clip(centres[y] + 0.02 * g.standard_normal((96, 4)), 0, 1)
+    T32 = rng.make_synthetic_labels(7, 3, 8, rng.UNIFORM01, kappa=1.0)
+    T = T32.astype(np.float64)
+    left = _rand_segment([4, 16, 8], osg.RELU_ALL, osg.MSE_SIL, seed=5, lr=0.05, momentum=0.9)
+    right = _rand_segment([8, 16, 3], osg.RELU_HIDDEN_IDENTITY_LAST, osg.SOFTMAX_XENT, seed=6, lr=0.1, momentum=0.9)
+    ll, rl = [], []
+    for ep in range(60):
+        a = b = 0.0
+        for s in range(0, 96, 32):
+            a += left.step(X[s:s + 32], y[s:s + 32], T)["loss"]
+            xin = rng.make_segment_inputs(9, T32, y[s:s + 32], s, 0.05).astype(np.float64)
+            b += right.step(xin, y[s:s + 32])["loss"]
+        ll.append(a / 3)
+        rl.append(b / 3)
+    assert ll[-1] < 0.1 * ll[0] and rl[-1] < 0.2 * rl[0]
+    pred = right.forward(left.forward(X)).argmax(axis=1)    # joined only now
+    assert (pred == y).mean() > 0.9
+
+
 # ---------------------------------------------------------------------------------
 # bf16 storage emulation
 # ---------------------------------------------------------------------------------
