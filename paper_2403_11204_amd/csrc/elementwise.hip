@@ -264,13 +264,25 @@ __device__ __forceinline__ void bias_grad_update_block(int block, const T* __res
   if (n >= N) return;
   const T* row = dZT + (size_t)n * ldt;
   const int Bv = (B + V - 1) / V;      // pads up to the chunk boundary are zero
-  float acc = 0.0f;
-  for (int c = lane; c < Bv; c += 64) {
-    const vec_t v = *(const vec_t*)(row + (size_t)c * V);
+  // four independent 16-byte loads per lane and trip, so that the row streams instead of crawling load by load;
+  // the partial sums are added in a fixed order
+  float a4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int c0 = lane; c0 < Bv; c0 += 256) {
+    vec_t v[4];
 #pragma unroll
-    for (int e = 0; e < V; ++e) acc += to_f32((T)v[e]);
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + 64 * u;
+      if (c < Bv) v[u] = *(const vec_t*)(row + (size_t)c * V);
+      else
+#pragma unroll
+        for (int e = 0; e < V; ++e) v[u][e] = from_f32<T>(0.0f);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int e = 0; e < V; ++e) a4[u] += to_f32((T)v[u][e]);
   }
-  acc = wave_sum(acc);
+  float acc = wave_sum((a4[0] + a4[1]) + (a4[2] + a4[3]));
   if (lane == 0) {
     db[n] = acc;
     float v = acc;
