@@ -11,6 +11,9 @@ namespace slp {
 // so that each row starts on a 16-byte boundary for both element types and a
 // 16-byte chunk never straddles two rows.  Pad elements are zero.
 constexpr int kLdAlign = 8;
+// What the library's own buffers use: rows that start on 128-byte boundaries (bf16), so that the 128-byte row
+// segment of a k-tile is one cache line, not two halves (measured 17 % on a product with rows 16 bytes off).
+constexpr int kLdRows = 64;
 inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
 
 enum Epilogue { EPI_FWD = 0, EPI_DGRAD = 1, EPI_WGRAD = 2 };
