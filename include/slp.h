@@ -163,8 +163,9 @@ int slp_segment_step(slp_segment* seg, const void* X /*device*/, const int32_t* 
 /* Forward only (Sec. 2: the stored response of the left partition; joining the
  * partitions): out[batch][last width], dense, handle dtype, device.  Parameters
  * are not changed; the activation workspace is overwritten (X and out themselves are
- * used in place of its first and last entries when their rows start on 16-byte
- * boundaries: width a multiple of 8, pointer 16-byte aligned).  Errors as for the step. */
+ * used in place of its first and last entries when their rows are aligned: X with a
+ * width that is a multiple of 64 on a 128-byte boundary, out with a width that is a
+ * multiple of 8 on a 16-byte boundary).  Errors as for the step. */
 int slp_segment_forward(slp_segment* seg, const void* X /*device*/, int batch, void* out /*device*/, slp_stream stream);
 
 /* ---- recovery phase (Sec. 5: the left partition is trained some more while the

@@ -528,7 +528,7 @@ int slp_segment_forward(slp_segment* seg, const void* X, int batch, void* out, s
   // the stored-response pass over a whole dataset (Sec. 2) is this call in a loop: no activation is kept for a
   // backward pass, and dense caller buffers whose rows start on 16-byte boundaries are used in place
   const int w0 = seg->widths[0], w = seg->widths[seg->L];
-  const bool x_direct = w0 % kLdAlign == 0 && ((uintptr_t)X & 15) == 0;
+  const bool x_direct = w0 % kLdRows == 0 && ((uintptr_t)X & 127) == 0;      // rows on cache-line boundaries, else the copy pays
   const bool out_direct = w % kLdAlign == 0 && ((uintptr_t)out & 15) == 0;
   if (!x_direct) {
     rc = ingest(seg, X, batch, false, st);
