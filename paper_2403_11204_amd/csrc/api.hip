@@ -106,7 +106,7 @@ int esize(const slp_segment* s) { return s->dtype == SLP_BF16 ? 2 : 4; }
 // captured steps hold lr, momentum, the label table and the buffer addresses by value
 void drop_graphs(slp_segment* s) {
   if (!s->graphs.empty()) (void)hipDeviceSynchronize();   // a replay may still be running; rare (set-up calls only)
-  for (auto& g : s->graphs) hipGraphExecDestroy(g.exec);
+  for (auto& g : s->graphs) (void)hipGraphExecDestroy(g.exec);
   s->graphs.clear();
 }
 bool relu_on(const slp_segment* s, int l) { return l < s->L || s->act == SLP_RELU_ALL; }
@@ -391,12 +391,12 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
 
 void slp_segment_destroy(slp_segment* seg) {
   if (!seg) return;
-  for (auto& r : seg->prof_log) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
-  for (auto e : seg->ev_pool) hipEventDestroy(e);
-  for (auto e : seg->ev_fork) hipEventDestroy(e);
-  if (seg->ev_join) hipEventDestroy(seg->ev_join);
+  for (auto& r : seg->prof_log) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto e : seg->ev_pool) (void)hipEventDestroy(e);
+  for (auto e : seg->ev_fork) (void)hipEventDestroy(e);
+  if (seg->ev_join) (void)hipEventDestroy(seg->ev_join);
   drop_graphs(seg);
-  if (seg->side) hipStreamDestroy(seg->side);
+  if (seg->side) (void)hipStreamDestroy(seg->side);
   delete seg;
 }
 
@@ -586,19 +586,19 @@ int slp_segment_step(slp_segment* seg, const void* X, const int32_t* targets, in
   hipGraph_t graph = nullptr;
   hipError_t e = hipStreamEndCapture(st, &graph);      // always ended, so that the stream is usable after an error
   if (rc || e != hipSuccess) {
-    if (graph) hipGraphDestroy(graph);
+    if (graph) (void)hipGraphDestroy(graph);
     return rc ? rc : fail(SLP_ERR_DEVICE, "hipStreamEndCapture: %s", hipGetErrorString(e));
   }
   StepGraph sg{X, targets, batch, loss_out, nullptr, seg->graph_tick};
   e = hipGraphInstantiate(&sg.exec, graph, nullptr, nullptr, 0);
-  hipGraphDestroy(graph);
+  (void)hipGraphDestroy(graph);
   if (e != hipSuccess) return fail(SLP_ERR_DEVICE, "hipGraphInstantiate: %s", hipGetErrorString(e));
   if (seg->graphs.size() >= kMaxStepGraphs) {          // evict the least recently used
     size_t v = 0;
     for (size_t i = 1; i < seg->graphs.size(); ++i)
       if (seg->graphs[i].used < seg->graphs[v].used) v = i;
     HIP_TRY(hipDeviceSynchronize());                   // its last replay may still be running
-    hipGraphExecDestroy(seg->graphs[v].exec);
+    (void)hipGraphExecDestroy(seg->graphs[v].exec);
     seg->graphs[v] = sg;
   } else {
     seg->graphs.push_back(sg);
@@ -718,8 +718,8 @@ int slp_probe_mfma_rate(int dtype, int iters, void* scratch, size_t scratch_byte
   if (e == hipSuccess) e = hipEventSynchronize(b);
   float t = 0.0f;
   if (e == hipSuccess) e = hipEventElapsedTime(&t, a, b);
-  hipEventDestroy(a);
-  hipEventDestroy(b);
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
   if (e != hipSuccess) return fail(SLP_ERR_DEVICE, "slp_probe_mfma_rate: %s", hipGetErrorString(e));
   *tflops = fl * cus * iters / (t * 1e-3) / 1e12;
   if (ms) *ms = t;
