@@ -124,3 +124,16 @@ def test_deep_config_interior_segment_full_size():
     Xd = api.make_segment_inputs(6, cut, torch.from_numpy(y).to(DEV), 0, 0.05, api.BF16)
     table = orng.make_synthetic_labels(22, classes, widths[-1], orng.NORMAL)
     run_full_size(widths, api.RELU_ALL, api.MSE_SIL, B, classes, Xd, y, table, datagen.uniform_weights(widths, seed=19))
+
+
+def test_largest_addressable_layer_float32():
+    # one 23168 x 23168 float32 layer: 2,147,024,896 bytes per matrix, 458,752 below the 2 GiB operand limit, so the
+    # 32-bit byte offsets of the matrix products run up to the end of their range; ragged batch
+    from test_gpu_parity import check_step, make_pair
+    widths, B = [23168, 23168], 200
+    X, y = datagen.class_mean_inputs(B, 7, dim=widths[0], seed=2)
+    table = orng.make_synthetic_labels(9, 7, widths[1], orng.UNIFORM_PM1)
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, api.F32, max_batch=B, lr=0.01, mom=0.9, wseed=23)
+    check_step(g, o, X, y, table, api.F32)
+    del g, o
+    torch.cuda.empty_cache()
