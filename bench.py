@@ -36,7 +36,7 @@ PEAK_TFLOPS = {api.BF16: 2516.6, api.F32: 157.3}     # dense MFMA peaks of MI355
 # one step of the default workload: rocprofv3 FETCH_SIZE / WRITE_SIZE passes scaled by a 1 GiB copy kernel in
 # the same process (profiles/comparison_config_gemm_hbm_traffic.md).  Valid for the kernel those passes ran;
 # set to None whenever csrc/gemm.hip changes until the passes are repeated.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {4: 5.51e9}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {4: None}
 MSE, CE = api.MSE_SIL, api.SOFTMAX_XENT
 ALL, LAST = api.RELU_ALL, api.RELU_HIDDEN_IDENTITY_LAST
 
@@ -235,7 +235,7 @@ def main():
         "step_tflops": flops_step / (ms * 1e-3) / 1e12,
         "step_frac_of_mfma_peak": flops_step / (ms * 1e-3) / 1e12 / peak,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.config), "kernel": "gemm_nt_kernel", "launches": gemm_n,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(args.config), "kernel": "gemm_nt_big_kernel" if args.config in (3, 4) else "gemm_nt_kernel", "launches": gemm_n,
                      "avg_launch_ms": gemm_ms / max(gemm_n, 1), "flops_per_launch": gemm_fl / max(gemm_n, 1)},
         "segment_bytes": [{"params": p, "workspace": w} for p, w in seg_bytes],
         "peak_hbm_bytes_torch": int(torch.cuda.max_memory_allocated()),

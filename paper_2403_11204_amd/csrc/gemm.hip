@@ -12,43 +12,34 @@
 // no transposition on the operand path.
 //
 // gfx950 mapping
-//   * NW wavefronts in a 2 x NW/2 grid; a wavefront owns a (BM/2) x (BN/(NW/2)) sub-tile as
-//     MIxNI MFMA 32x32 blocks, accumulators in registers.  The 256x256 tile runs with 8
-//     wavefronts (128x64 each, 128 accumulator registers, two wavefronts per SIMD so that one
-//     can issue MFMAs while the other waits on LDS or the barrier): measured 4 % faster than
-//     4 wavefronts of 128x128 in spite of 50 % more LDS reads, and its epilogues do not spill.
-//     The 64x64 tile runs with 4 wavefronts; the 128x128 tile with 8 (64x32 each) in its four-stage
-//     form and with 4 (64x64 each) in its two-stage form, where two workgroups share a compute unit.
-//   * bf16: v_mfma_f32_32x32x16_bf16, one per 16-byte chunk pair; float32:
-//     v_mfma_f32_32x32x2_f32, four per 16-byte chunk pair.  A k-tile is 128 bytes
-//     per row for both types (64 bf16 / 32 float), so loads, LDS layout and
-//     addressing are byte-identical for the two types.
-//   * global -> LDS directly (buffer_load_dwordx4 ... lds): no staging registers and
-//     no ds_write instructions (a burst of 16-byte LDS writes stalls the LDS pipe for
-//     ~13 cycles per wavefront instruction; measured, it was the largest stall).
-//     Out-of-range rows and k-tail chunks read as zero through the buffer resource's
-//     range check, so ragged M, N and K need no branches.
-//   * NS LDS stages of (BM+BN) x 128 bytes (two for the 256x256 tile, four for the small ones); the
-//     loads of tile k+NS are issued as soon as the barrier after sub-step 2 of tile k has freed
-//     its stage; one barrier per k-tile.
-//   * every k-tile is 4 sub-steps of MIxNI MFMAs; the fragments of sub-step s+1 are read
-//     from LDS while sub-step s multiplies, and the source order "2 LDS reads, 2 loads,
-//     2 MFMAs" is pinned with scheduling fences, because the compiler's own schedule
-//     serialises LDS latency with the matrix pipe.
-//   * LDS rows are 128 bytes and the LDS has 64 banks x 4 bytes: a ds_read_b128 is served
-//     16 lanes at a time, i.e. 16 consecutive rows of one k-chunk.  Physical chunk =
-//     chunk ^ ((row >> 1) & 7) spreads those 16 rows over all 64 banks (measured 5.8 vs
-//     8.0 cycles per wavefront read for the naive (row & 7) swizzle).  The hardware writes
-//     lane l of an LDS-direct load at base + 16 l, so the swizzle is applied on the global
-//     side: each lane fetches the chunk that belongs at its physical position.
+//   * bf16: v_mfma_f32_16x16x32_bf16 (16x16 blocks; a register-only loop of it sustains 2110 TFLOP/s under the
+//     chip's power limit, the 32x32x16 form 1850); float32: v_mfma_f32_32x32x2_f32, four per 16-byte chunk pair.
+//     A k-tile is 128 bytes per row for both types (64 bf16 / 32 float), so loads, LDS layout and addressing
+//     are byte-identical for the two types.
+//   * global -> LDS directly (buffer_load_dwordx4 ... lds): no staging registers and no ds_write instructions.
+//     Out-of-range rows and k-tail chunks read as zero through the buffer resource's range check, so ragged
+//     M, N and K need no branches.
+//   * LDS rows are 128 bytes and the LDS has 64 banks x 4 bytes: a ds_read_b128 is served 16 lanes at a time,
+//     i.e. 16 consecutive rows of one k-chunk.  Physical chunk = chunk ^ ((row >> 1) & 7) spreads those 16 rows
+//     over all 64 banks (no conflicts counted).  The hardware writes lane l of an LDS-direct load at
+//     base + 16 l, so the swizzle is applied on the global side: each lane fetches the chunk that belongs at its
+//     physical position.
+//   * big products (256x256 tile, bf16): gemm_nt_big_kernel, 8 wavefronts of 128x64, two LDS stages of 64 KB,
+//     the loads of a k-tile issued evenly over the whole k-tile (two barriers per k-tile free the stage piecewise);
+//     see the comment on that kernel.
+//   * everything else (float32, smaller tiles): gemm_nt_kernel, NW wavefronts in a 2 x NW/2 grid, a wavefront
+//     owns a (BM/2) x (BN/(NW/2)) sub-tile; NS LDS stages of (BM+BN) x 128 bytes (two for the 256x256 tile, four
+//     for the small ones); one barrier per k-tile, after which the loads of tile k+NS are issued; a k-tile is 4
+//     pipeline units, the fragments of unit u+1 are read from LDS while unit u multiplies.
+//   * in both kernels the source order "a few LDS reads / loads, a few MFMAs" is pinned with scheduling fences,
+//     because the compiler's own schedule serialises LDS latency with the matrix pipe.
 //   * epilogue: a lane holds 4 consecutive rows of one output column per accumulator register quad, which
 //     is one vector store into the transposed output; for the row-major output the quad of lanes holding
 //     4 adjacent columns transposes its 4x4 block with DPP moves, after which a lane holds 4 consecutive
 //     columns of one row: one vector store as well (2 stores per quad instead of 5).
 //   * workgroup -> tile: consecutive workgroup ids go round-robin over the 8 XCDs, so
 //     ids are first regrouped per XCD (each XCD gets a contiguous range of tiles and
-//     its own 4 MB L2 sees a compact set of operand rows: measured L2 hit rate 79%), then
-//     walked in column-major groups of 8 tile-rows.
+//     its own 4 MB L2 sees a compact set of operand rows), then walked in column-major groups of 8 tile-rows.
 #include "slp_kernels.h"
 
 namespace slp {
@@ -69,6 +60,7 @@ template <typename T> struct Chunk;
 template <> struct Chunk<bf16> { static constexpr int elems = 8; };
 template <> struct Chunk<float> { static constexpr int elems = 4; };
 
+// 32x32 block forms (one 16-byte chunk pair per call), used by the contraction-split kernel for small products
 __device__ __forceinline__ void mma_chunk(f32x16& acc, const u32x4& a, const u32x4& b, bf16*) {
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
 }
@@ -77,6 +69,27 @@ __device__ __forceinline__ void mma_chunk(f32x16& acc, const u32x4& a, const u32
 #pragma unroll
   for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[q], bfv[q], acc, 0, 0, 0);
 }
+
+// MFMA geometry per element type.  bf16: v_mfma_f32_16x16x32_bf16 (a 16x16 block over 32 k = 4 chunks per row; the
+// block's 4 accumulator registers hold rows 4*(lane/16)..+3 of column lane%16); float32: v_mfma_f32_32x32x2_f32, four
+// per chunk pair.  MB = block edge, AH = parts the A fragments of one k-sub-step are read in (pipeline units).
+template <typename T> struct Mma;
+template <> struct Mma<bf16> {
+  static constexpr int MB = 16, AH = 2, ACC = 4;
+  typedef f32x4 acc_t;
+  static __device__ __forceinline__ void mma(acc_t& acc, const u32x4& a, const u32x4& b) {
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+  }
+};
+template <> struct Mma<float> {
+  static constexpr int MB = 32, AH = 1, ACC = 16;
+  typedef f32x16 acc_t;
+  static __device__ __forceinline__ void mma(acc_t& acc, const u32x4& a, const u32x4& b) {
+    const f32x4 af = __builtin_bit_cast(f32x4, a), bfv = __builtin_bit_cast(f32x4, b);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[q], bfv[q], acc, 0, 0, 0);
+  }
+};
 
 template <typename T> struct Vec4;
 template <> struct Vec4<bf16> { typedef bf16x4 type; };
@@ -162,7 +175,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   constexpr int RPL = 8 * NW;                  // tile rows covered by one load instruction of the whole workgroup
   constexpr int LA = BM / RPL, LB = BN / RPL;  // 16-byte loads per thread per k-tile
-  constexpr int WTM = BM / 2, WTN = BN / (NW / 2), MI = WTM / 32, NI = WTN / 32;
+  typedef Mma<T> MM;
+  constexpr int MB = MM::MB, AH = MM::AH;
+  constexpr int CPS = 64 / MB;                 // 16-byte chunks per row that one k-sub-step consumes
+  constexpr int KSUB = 8 / CPS;                // k-sub-steps per k-tile
+  constexpr int UNITS = KSUB * AH;             // pipeline units per k-tile
+  constexpr int WTM = BM / 2, WTN = BN / (NW / 2), MI = WTM / MB, NI = WTN / MB, MIH = MI / AH;
+  static_assert(MI % AH == 0 && UNITS % 2 == 0 && KSUB % 2 == 0, "buffer parity must repeat from tile to tile");
 
   // ---- workgroup -> tile ------------------------------------------------------------
   const int tilesM = (g.M + BM - 1) / BM, tilesN = (g.N + BN - 1) / BN;
@@ -182,7 +201,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
   const int wm = w & 1, wn = w >> 1;
-  const int half = lane >> 5, l32 = lane & 31;
+  const int lgrp = lane / MB, lrow = lane % MB;
 
   // ---- global load addressing --------------------------------------------------------
   const int Kr = (g.K + CH - 1) / CH * CH;   // chunk-granular contraction length
@@ -206,33 +225,39 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
   const int kc = pchunk;
 
   // ---- fragment addressing -------------------------------------------------------------
-  const uint32_t fragA = (uint32_t)((wm * WTM + l32) * 128);
-  const uint32_t fragB = (uint32_t)(A_BYTES + (wn * WTN + l32) * 128);
-  uint32_t xo[4];
+  const uint32_t fragA = (uint32_t)((wm * WTM + lrow) * 128);
+  const uint32_t fragB = (uint32_t)(A_BYTES + (wn * WTN + lrow) * 128);
+  uint32_t xo[KSUB];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) xo[kk] = (uint32_t)(((kk * 2 + half) ^ ((lane >> 1) & 7)) << 4);
+  for (int kk = 0; kk < KSUB; ++kk) xo[kk] = (uint32_t)(((kk * CPS + lgrp) ^ ((lane >> 1) & 7)) << 4);
 
-  f32x16 acc[MI][NI];
+  typename MM::acc_t acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+      for (int r = 0; r < MM::ACC; ++r) acc[i][j][r] = 0.0f;
 
-  u32x4 af[2][MI], bfr[2][NI];
+  // Pipeline unit u of a k-tile = k-sub-step u / AH, part u % AH of the wavefront's rows: MIH A fragments (buffer u & 1)
+  // against the sub-step's NI B fragments (buffer (u / AH) & 1, read together with part 0).
+  u32x4 af[2][MIH], bfr[2][NI];
   // Every k-sub-step is written out as small groups "a few loads/stores + a few MFMAs",
   // fenced so that the compiler keeps the interleaving: the matrix pipe always has work
   // queued while LDS and global traffic for later sub-steps is in flight.
-  constexpr int NRD = MI + NI;                               // fragment reads per k-sub-step
+  constexpr int NRD = MIH + NI;                              // most fragment reads any unit needs (those with part 0)
   constexpr int NLD = LA + LB;                               // global loads / LDS writes per k-tile
-  constexpr int NMM = MI * NI;                               // accumulator blocks
-  auto read_one = [&](int stage, int kk, int set, int r) {
+  constexpr int NMM = MIH * NI;                              // MFMA groups per unit
+  auto reads_of = [](int u) { return MIH + (u % AH == 0 ? NI : 0); };
+  auto read_one = [&](int stage, int u, int r) {             // read r of the fragments unit u multiplies
     const unsigned char* sb = smem + stage * STAGE;
-    if (r < MI) af[set][r] = *(const u32x4*)(sb + fragA + r * 32 * 128 + xo[kk]);
-    else bfr[set][r - MI] = *(const u32x4*)(sb + fragB + (r - MI) * 32 * 128 + xo[kk]);
+    const int kk = u / AH, h = u % AH;
+    if (r < MIH) af[u & 1][r] = *(const u32x4*)(sb + fragA + (h * MIH + r) * MB * 128 + xo[kk]);
+    else bfr[kk & 1][r - MIH] = *(const u32x4*)(sb + fragB + (r - MIH) * MB * 128 + xo[kk]);
   };
-  auto mma_one = [&](int set, int m) { mma_chunk(acc[m / NI][m % NI], af[set][m / NI], bfr[set][m % NI], (T*)nullptr); };
+  auto mma_one = [&](int u, int m) {
+    MM::mma(acc[(u % AH) * MIH + m / NI][m % NI], af[u & 1][m / NI], bfr[(u / AH) & 1][m % NI]);
+  };
   auto gload_one = [&](int kt, int stage, int i) {
     const bool in_k = kt * BK + kc * CH < Kr;      // past the end of K every load becomes a zero fill
     const uint32_t koff = (uint32_t)kt * 128u;
@@ -255,18 +280,18 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
   __builtin_amdgcn_s_waitcnt(VMCNT((NS - 1) * NLD));
   __syncthreads();
 #pragma unroll
-  for (int r = 0; r < NRD; ++r) read_one(0, 0, 0, r);
-  auto rd_lo = [](int g) { return 2 * g < NRD ? 2 * g : NRD; };
+  for (int r = 0; r < NRD; ++r) read_one(0, 0, r);
+  auto rd_lo = [](int g, int n) { return 2 * g < n ? 2 * g : n; };
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt % NS, nxt = (kt + 1) % NS;
 #pragma unroll
-    for (int kk = 0; kk < 3; ++kk) {
+    for (int u = 0; u < UNITS - 1; ++u) {
 #pragma unroll
       for (int g = 0; g < NRD; ++g) {
 #pragma unroll
-        for (int r = rd_lo(g); r < rd_lo(g + 1); ++r) read_one(cur, kk + 1, (kk + 1) & 1, r);
+        for (int r = rd_lo(g, reads_of(u + 1)); r < rd_lo(g + 1, reads_of(u + 1)); ++r) read_one(cur, u + 1, r);
 #pragma unroll
-        for (int m = g * NMM / NRD; m < (g + 1) * NMM / NRD; ++m) mma_one(kk & 1, m);
+        for (int m = g * NMM / NRD; m < (g + 1) * NMM / NRD; ++m) mma_one(u, m);
         SLP_FENCE();
       }
     }
@@ -286,11 +311,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 #pragma unroll
     for (int g = 0; g < NRD; ++g) {
 #pragma unroll
-      for (int r = rd_lo(g); r < rd_lo(g + 1); ++r) read_one(nxt, 0, 0, r);
+      for (int r = rd_lo(g, NRD); r < rd_lo(g + 1, NRD); ++r) read_one(nxt, 0, r);
 #pragma unroll
       for (int i = g * NLD / NRD; i < (g + 1) * NLD / NRD; ++i) gload_one(kt + NS, cur, i);
 #pragma unroll
-      for (int m = g * NMM / NRD; m < (g + 1) * NMM / NRD; ++m) mma_one(1, m);
+      for (int m = g * NMM / NRD; m < (g + 1) * NMM / NRD; ++m) mma_one(UNITS - 1, m);
       SLP_FENCE();
     }
   }
@@ -298,26 +323,208 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 #undef SLP_FENCE
 
   // ---- epilogue ----------------------------------------------------------------------------
-  // Accumulator layout of the 32x32 MFMA: lane holds column n = lane & 31 and, in
-  // register r, row 8*(r/4) + 4*(lane/32) + (r%4): four consecutive rows per register
-  // quad, which is what makes the transposed store a vector store.
+  // Accumulator layout of an MB x MB block: lane holds column n = lane % MB and, in register r, row
+  // (64 / MB * 4) * (r / 4) + 4 * (lane / MB) + (r % 4): four consecutive rows per register quad, which is what
+  // makes the transposed store a vector store.
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
-    const int n = n0 + wn * WTN + j * 32 + l32;
+    const int n = n0 + wn * WTN + j * MB + lrow;
     float bias = 0.0f;
     if (EPI == EPI_FWD && n < g.N) bias = g.bias[n];
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < MM::ACC / 4; ++q) {
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-        store_quad<T, EPI>(g, n, m0 + wm * WTM + i * 32 + 8 * q + 4 * half, bias, v, lane);
+        store_quad<T, EPI>(g, n, m0 + wm * WTM + i * MB + (256 / MB) * q + 4 * lgrp, bias, v, lane);
         // keep the scheduler from hoisting every block's address arithmetic and mask
         // loads to the top of the epilogue (that spills registers)
         __builtin_amdgcn_sched_barrier(0);
       }
+    }
+  }
+#endif
+}
+
+// Big bf16 products: 256x256 tile, NW = 8 wavefronts in a 2 x 4 grid (128 x 64 each; NW = 4, 128 x 128 each with the
+// accumulators in AGPRs, is kept compilable: measured equal, but its data-gradient epilogue spills),
+// v_mfma_f32_16x16x32_bf16, two LDS stages of 64 KB.
+// A k-tile (64 k) is 4 units: (row half h, k-sub-step kk) in the order (0,0) (0,1) (1,0) (1,1), each 4 A fragments
+// against the NB B fragments of the sub-step.  The B fragments of a k-tile stay in registers for the whole tile, the A
+// fragments are read one unit ahead.  That order frees LDS early: after unit 0 nothing of this stage's B rows and h=0
+// A rows is needed any more, after unit 2 the h=1 A rows are free too.  Two barriers per k-tile (X after unit 0, Y
+// after unit 2) let the LDS-direct loads of tile kt+2 be issued evenly over the whole k-tile, a quarter of them per
+// unit.  Issued in one burst after a single barrier (as gemm_nt_kernel does) they cost the unit that issues them 3x its
+// MFMA time: measured per unit with the cycle counter, 570 / 581 / 498 / 1578 cycles against 512 of MFMAs each.
+// Sustained on 8192x16384x16384: 1295-1315 -> 1365-1415 TFLOP/s.
+template <int EPI, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef bf16 T;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int BM = 256, BN = 256, ES = 2, CH = 8, BK = 64;
+  constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
+  constexpr int WN = NW / 2;             // wavefront columns
+  constexpr int WTN = BN / WN;           // columns per wavefront (128 or 64)
+  constexpr int NB = WTN / 16;           // B fragments per sub-step (8 or 4)
+  constexpr int RPL = 8 * NW;            // rows one load instruction of the workgroup covers (32 or 64)
+  constexpr int NBLK = 256 / RPL;        // row blocks (= loads per lane) per operand per k-tile (8 or 4)
+  constexpr int NL = 2 * NBLK;           // loads per lane per k-tile (16 or 8)
+  constexpr int LPU = NL / 4;            // loads per unit (4 or 2)
+  constexpr int NSLOT = 2 * NB;          // slots of 2 MFMAs per unit (16 or 8)
+
+  const int tilesM = (g.M + BM - 1) / BM, tilesN = (g.N + BN - 1) / BN;
+  const int total = tilesM * tilesN;
+  int tid;
+  {
+    const int pid = blockIdx.x, xcd = pid % kXcds, q = pid / kXcds;
+    const int base = total / kXcds, rem = total % kXcds;
+    tid = xcd * base + (xcd < rem ? xcd : rem) + q;
+  }
+  const int group_m = g.group_m > 0 ? g.group_m : kGroupM;
+  const int width = group_m * tilesN;
+  const int group = tid / width, first_m = group * group_m;
+  const int gsz = (tilesM - first_m) < group_m ? (tilesM - first_m) : group_m;
+  const int tm = first_m + (tid % width) % gsz, tn = (tid % width) / gsz;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int wm = w & 1, wn = w >> 1;
+  const int lgrp = lane >> 4, lrow = lane & 15;
+
+  const int Kr = (g.K + CH - 1) / CH * CH;
+  const __amdgpu_buffer_rsrc_t rsrcA =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.A), 0, (int)((size_t)g.M * g.lda * ES), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.B), 0, (int)((size_t)g.N * g.ldb * ES), 0x00020000);
+  // load i of the workgroup fills rows [RPL i, RPL i + RPL) of an operand's 256; wavefront w rows 8w..8w+7 of those
+  const int prow = w * 8 + (lane >> 3);
+  const int pchunk = (lane & 7) ^ ((prow >> 1) & 7);
+  uint32_t voffA[NBLK], voffB[NBLK];
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i) voffA[i] = (uint32_t)(((size_t)(m0 + prow + RPL * i) * g.lda + pchunk * CH) * ES);
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i) voffB[i] = (uint32_t)(((size_t)(n0 + prow + RPL * i) * g.ldb + pchunk * CH) * ES);
+  typedef __attribute__((address_space(3))) void* lds_ptr_t;
+  const uint32_t lds_wave = (uint32_t)__builtin_amdgcn_readfirstlane(w * 8 * 128);
+  const int kc = pchunk;
+
+  const uint32_t fragA = (uint32_t)((wm * 128 + lrow) * 128);
+  const uint32_t fragB = (uint32_t)(A_BYTES + (wn * WTN + lrow) * 128);
+  uint32_t xo[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) xo[kk] = (uint32_t)(((kk * 4 + lgrp) ^ ((lane >> 1) & 7)) << 4);
+
+  f32x4 acc[8][NB];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+
+  u32x4 af[2][4], bfr[2][NB];
+  // The NL loads of a k-tile in issue order: first the 3/4 that fill the rows free after unit 0 (A rows of half h = 0 of
+  // both wavefront rows, all B rows), then the A rows of half h = 1.  Entry < NBLK: A row block, else B row block.
+  auto gload = [&](int kt, int stage, int idx) {
+    const bool in_k = kt * BK + kc * CH < Kr;
+    const uint32_t koff = (uint32_t)kt * 128u;
+    constexpr int order4[16] = {0, 8, 1, 9, 4, 10, 5, 11, 12, 13, 14, 15, 2, 3, 6, 7};
+    constexpr int order8[8] = {0, 4, 2, 5, 6, 7, 1, 3};
+    const int o = NW == 4 ? order4[idx] : order8[idx % 8];
+    if (o < NBLK)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(smem + stage * STAGE + lds_wave + o * RPL * 128), 16,
+                                               in_k ? voffA[o] + koff : kOutOfRange, 0, 0, 0);
+    else
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)(smem + stage * STAGE + A_BYTES + lds_wave + (o - NBLK) * RPL * 128), 16,
+                                               in_k ? voffB[o - NBLK] + koff : kOutOfRange, 0, 0, 0);
+  };
+  auto read_a = [&](int stage, int h, int kk, int buf, int r) {
+    af[buf][r] = *(const u32x4*)(smem + stage * STAGE + fragA + (h * 4 + r) * 16 * 128 + xo[kk]);
+  };
+  auto read_b = [&](int stage, int kk, int c) {
+    bfr[kk][c] = *(const u32x4*)(smem + stage * STAGE + fragB + c * 16 * 128 + xo[kk]);
+  };
+  auto mma = [&](int h, int kk, int buf, int m) {   // m = 0..4 NB - 1: A fragment m / NB against B fragment m % NB
+    acc[h * 4 + m / NB][m % NB] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+        __builtin_bit_cast(bf16x8, af[buf][m / NB]), __builtin_bit_cast(bf16x8, bfr[kk][m % NB]), acc[h * 4 + m / NB][m % NB], 0, 0, 0);
+  };
+#define VMCNT(n) ((((n) & 15) | 0x0F70 | (((n) >> 4) << 14)))
+#define SLP_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define SLP_BARRIER(n)                                              \
+  do {                                                              \
+    __builtin_amdgcn_s_waitcnt(VMCNT(n) & 0xF0FF);                  \
+    asm volatile("" ::: "memory");                                  \
+    __builtin_amdgcn_s_barrier();                                   \
+    asm volatile("" ::: "memory");                                  \
+  } while (0)
+
+  const int nk = (Kr + BK - 1) / BK;
+  // A slot = up to two memory operations followed by 2 MFMAs.  Operation codes: 0 none, 1 + r: read A fragment r,
+  // 5 + c: read B fragment c, 13 + i: the unit's load i.  Reads are ordered by first use in the next unit (A0, B0.., A1..).
+  struct Slot { int a, b; };
+  constexpr Slot kWide4[16] = {{1, 0}, {5, 0}, {6, 0}, {13, 0}, {7, 0}, {8, 0}, {9, 0}, {14, 0},
+                               {10, 0}, {11, 0}, {12, 0}, {15, 0}, {2, 0}, {3, 0}, {4, 0}, {16, 0}};
+  constexpr Slot kNarrow4[16] = {{1, 0}, {0, 0}, {13, 0}, {0, 0}, {2, 0}, {0, 0}, {14, 0}, {0, 0},
+                                 {3, 0}, {0, 0}, {15, 0}, {0, 0}, {4, 0}, {0, 0}, {16, 0}, {0, 0}};
+  constexpr Slot kWide8[8] = {{1, 5}, {6, 0}, {13, 0}, {7, 0}, {8, 2}, {14, 0}, {3, 0}, {4, 0}};
+  constexpr Slot kNarrow8[8] = {{1, 0}, {13, 0}, {2, 0}, {0, 0}, {3, 0}, {14, 0}, {4, 0}, {0, 0}};
+  // one unit: fragments of (h, kk) from af[buf], bfr[kk]; reads for the next unit (A fragments of (rh, rk) into
+  // af[buf ^ 1], and, in a wide unit, the B fragments of sub-step rk) from stage rs; loads lbase.. of tile lkt into stage ls
+  auto unit = [&](bool wide, int h, int kk, int buf, int rs, int rh, int rk, int lkt, int ls, int lbase) {
+#pragma unroll
+    for (int sl = 0; sl < NSLOT; ++sl) {
+      const Slot so = NW == 4 ? (wide ? kWide4[sl % 16] : kNarrow4[sl % 16]) : (wide ? kWide8[sl % 8] : kNarrow8[sl % 8]);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int op = q == 0 ? so.a : so.b;
+        if (op >= 1 && op <= 4) read_a(rs, rh, rk, buf ^ 1, op - 1);
+        else if (op >= 5 && op <= 12) read_b(rs, rk, op - 5);
+        else if (op >= 13) gload(lkt, ls, lbase + op - 13);
+      }
+      mma(h, kk, buf, 2 * sl); mma(h, kk, buf, 2 * sl + 1);
+      SLP_FENCE();
+    }
+  };
+  // prologue: tile 0 completely and the first 3/4 of the loads of tile 1
+#pragma unroll
+  for (int i = 0; i < NL; ++i) gload(0, 0, i);
+#pragma unroll
+  for (int i = 0; i < 3 * LPU; ++i) gload(1, 1, i);
+  SLP_BARRIER(3 * LPU);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) read_a(0, 0, 0, 0, r);
+#pragma unroll
+  for (int c = 0; c < NB; ++c) read_b(0, 0, c);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1, nxt = cur ^ 1;
+    unit(true, 0, 0, 0, cur, 0, 1, kt + 1, nxt, 3 * LPU);     // reads A(0,1), B(1); last quarter of tile kt+1's loads
+    SLP_BARRIER(4 * LPU);   // X: this tile's h=1 A rows have landed; nobody reads B / h=0 A rows of stage cur any more
+    unit(false, 0, 1, 1, cur, 1, 0, kt + 2, cur, 0);          // reads A(1,0); first quarter of tile kt+2's loads
+    unit(false, 1, 0, 0, cur, 1, 1, kt + 2, cur, LPU);        // reads A(1,1); second quarter
+    SLP_BARRIER(3 * LPU);   // Y: B and h=0 A rows of tile kt+1 have landed in stage nxt; h=1 A rows of stage cur are free
+    unit(true, 1, 1, 1, nxt, 0, 0, kt + 2, cur, 2 * LPU);     // reads next tile's A(0,0), B(0); third quarter
+  }
+  __builtin_amdgcn_s_waitcnt(VMCNT(0));
+#undef SLP_FENCE
+#undef SLP_BARRIER
+#undef VMCNT
+
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int n = n0 + wn * WTN + j * 16 + lrow;
+    float bias = 0.0f;
+    if (EPI == EPI_FWD && n < g.N) bias = g.bias[n];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e];
+      store_quad<T, EPI>(g, n, m0 + wm * 128 + i * 16 + 4 * lgrp, bias, v, lane);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 #endif
@@ -461,12 +668,38 @@ hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-// LDS stages (loads run stages-1 k-tiles ahead of the multiplies): a 256x256 tile fills LDS with two, and its k-tile
-// is ~1 us of MFMAs, enough to cover the loads of the next one; the k-tiles of the small tiles are 4-16x shorter.
+constexpr int kBigWaves = 8;
+constexpr int kBigSmem = 2 * 512 * 128;
+
+template <int EPI>
+hipError_t configure_big() {
+  static bool configured = false;   // one attribute call per instantiation
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_nt_big_kernel<EPI, kBigWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigSmem);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  return hipSuccess;
+}
+
+template <int EPI>
+hipError_t launch_big(const GemmArgs& g, hipStream_t s) {
+  constexpr int smem = kBigSmem;
+  hipError_t e = configure_big<EPI>();
+  if (e != hipSuccess) return e;
+  const int tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
+  hipLaunchKernelGGL((gemm_nt_big_kernel<EPI, kBigWaves>), dim3(tiles), dim3(kBigWaves * 64), smem, s, g);
+  return hipGetLastError();
+}
+
+// LDS stages of gemm_nt_kernel (loads run stages-1 k-tiles ahead of the multiplies): a 256x256 tile fills LDS with two;
+// the k-tiles of the small tiles are 4-16x shorter, too short to cover the loads of the next one, so they keep four.
 template <typename T, int EPI>
 hipError_t launch_cfg(int cfg, const GemmArgs& g, hipStream_t s) {
   switch (cfg) {
-    case 0: return launch_one<T, 256, 256, EPI, 8, 2>(g, s);
+    case 0:
+      if constexpr (sizeof(T) == 2) return launch_big<EPI>(g, s);
+      else return launch_one<T, 256, 256, EPI, 8, 2>(g, s);
     case 1: return launch_one<T, 128, 128, EPI, 8, 4>(g, s);     // 8 wavefronts of 64x32: +5-10 % over 4 of 64x64 here
     case kCfg128TwoStage: return launch_one<T, 128, 128, EPI, 4, 2>(g, s);
     default: return launch_one<T, 64, 64, EPI, 4, 4>(g, s);
@@ -504,7 +737,9 @@ hipError_t launch_epi(int epi, int cfg, const GemmArgs& g, hipStream_t s) {
 
 template <typename T, int EPI>
 hipError_t configure_epi() {
-  hipError_t e = configure_one<T, 256, 256, EPI, 8, 2>();
+  hipError_t e;
+  if constexpr (sizeof(T) == 2) e = configure_big<EPI>();
+  else e = configure_one<T, 256, 256, EPI, 8, 2>();
   if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 8, 4>();
   if (e == hipSuccess) e = configure_one<T, 128, 128, EPI, 4, 2>();
   if (e == hipSuccess) e = configure_one<T, 64, 64, EPI, 4, 4>();
