@@ -183,6 +183,7 @@ def main():
                     help="first run one plain 1 GiB -> 1 GiB elementwise copy kernel (scale reference for HBM byte counters)")
     ap.add_argument("--eager", action="store_true", help="configs 0-2: launch every kernel of a step instead of replaying graphs")
     ap.add_argument("--serial", action="store_true", help="config 3: run the four segments one after another on one stream")
+    ap.add_argument("--concurrent", action="store_true", help="run the segments at the same time on a stream each (the default of config 3)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (segments are independent jobs; no collectives exist): use --gpus 1")
@@ -191,6 +192,8 @@ def main():
     cfg = dict(CONFIGS[args.config])
     if args.serial:
         cfg["streams"] = False
+    if args.concurrent:
+        cfg["streams"] = True
     big = args.config in (3, 4)
     steps = args.steps if args.steps is not None else (20 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)

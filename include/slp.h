@@ -96,8 +96,10 @@ int slp_make_segment_inputs(uint64_t seed, const float* table /*device*/, int cl
  * The handle is host memory owned by the library until slp_segment_destroy.
  * Errors: SLP_ERR_ARG (null pointers, n_widths < 2 or > 65, a width outside [1, 2^20], unknown enum, max_batch
  * outside [1, 2^24], lr < 0, momentum outside [0,1)); SLP_ERR_SHAPE when a matrix cannot be
- * addressed with 32-bit byte offsets: a weight matrix (float32, leading dimension rounded up
- * to 64) or an activation matrix (max_batch x width in the handle's dtype) of 2 GiB or more. */
+ * addressed with 32-bit byte offsets: a weight matrix (float32) or an activation matrix (max_batch x width
+ * in the handle's dtype, and its transposed copy) of 2 GiB or more, counted with the library's leading
+ * dimensions: the row length rounded up to a multiple of 64 elements, plus 192 elements where that row would
+ * be a multiple of 4 KB in the handle's dtype. */
 int slp_segment_create(const int* widths /*host*/, int n_widths, int act, int loss, const slp_opts* opts /*host*/,
                        slp_segment** out);
 void slp_segment_destroy(slp_segment* seg);

@@ -328,11 +328,11 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
 
   slp_segment* s = new slp_segment();
   s->L = n_widths - 1; s->act = act; s->loss = loss; s->dtype = opts->dtype; s->max_batch = opts->max_batch;
-  s->ldb = round_up(opts->max_batch, kLdRows);
+  s->ldb = internal_ld(opts->max_batch, opts->dtype == SLP_BF16 ? 2 : 4);
   s->lr = opts->lr; s->mu = opts->momentum;
   s->input_grad = opts->input_grad != 0;
   s->widths.assign(widths, widths + n_widths);
-  for (int w : s->widths) s->ldw.push_back(round_up(w, kLdRows));
+  for (int w : s->widths) s->ldw.push_back(internal_ld(w, opts->dtype == SLP_BF16 ? 2 : 4));
   const size_t es = esize(s);
 
   // every operand is addressed with 32-bit byte offsets below 2 GiB

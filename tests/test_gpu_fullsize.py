@@ -140,9 +140,10 @@ def test_largest_addressable_layer_float32():
 
 
 def test_largest_addressable_batch_bf16():
-    # 65472 rows of 16384 bf16 values: 2,145,386,496 bytes per activation matrix, one 64-row step below the 2 GiB
-    # operand limit (65536 rows are rejected at create time); one 16384 x 16384 layer
-    widths, B, classes = [16384, 16384], 65472, 10
+    # 64768 rows of 16384 bf16 values in rows of 16576 elements (the library skews rows that would be a multiple of
+    # 4 KB): 2,147,188,736 bytes per activation matrix, one 64-row step below the 2 GiB operand limit (64832 rows are
+    # rejected at create time); one 16384 x 16384 layer
+    widths, B, classes = [16384, 16384], 64768, 10
     _, y = datagen.class_mean_inputs(B, classes, dim=8, seed=1)
     cut = api.make_synthetic_labels(41, classes, widths[0], api.UNIFORM_PM1, 1.0, api.F32)
     Xd = api.make_segment_inputs(7, cut, torch.from_numpy(y).to(DEV), 0, 0.05, api.BF16)
