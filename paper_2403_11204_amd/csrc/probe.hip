@@ -1,6 +1,6 @@
 // Matrix-pipe issue probe: the same MFMA instructions, accumulator count and occupancy as the
-// 256x256 product kernel (8 wavefronts per workgroup, one workgroup per compute unit, 8
-// independent 32x32 accumulator blocks per wavefront), but with operands that never leave
+// 256x256 product kernels (8 wavefronts per workgroup, one workgroup per compute unit, 128
+// accumulator registers per lane in independent blocks), but with operands that never leave
 // registers -- no LDS, no global loads, no barriers.  Its rate is what the chip sustains on
 // this instruction mix under its power limit, which is the ceiling the product kernel can be
 // compared with next to the published peak (the clock drops under sustained MFMA load, and
@@ -30,56 +30,77 @@ __device__ __forceinline__ float one_f32(uint32_t h) {
   return __builtin_bit_cast(float, ((h & 1u) << 31) | ((124u + ((h >> 1) & 3u)) << 23) | ((h >> 3) & 0x7fffffu));
 }
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// bf16: 8 x 4 blocks of v_mfma_f32_16x16x32_bf16 per wavefront (the 128 x 64 sub-tile of the big product kernel),
+// float32: 4 x 2 blocks of v_mfma_f32_32x32x2_f32 (the generic kernel's); 128 accumulator registers either way.
 template <int DT>
 __global__ __launch_bounds__(512) void mfma_issue_kernel(int iters, float* sink) {
   const uint32_t id = blockIdx.x * 512u + threadIdx.x;
-  f32x16 acc[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
-  // two operand sets (4 "A" and 2 "B" fragments each), alternated so that operand lines toggle
-  u32x4 a[2][4], b[2][2];
+  constexpr int NA = DT == SLP_BF16 ? 8 : 4, NB = DT == SLP_BF16 ? 4 : 2;
+  // two operand sets (NA "A" and NB "B" fragments each), alternated so that operand lines toggle
+  u32x4 a[2][NA], b[2][NB];
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NA; ++i)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const uint32_t h = mix(id * 64u + s * 32u + i * 4u + q + 1u);
+        const uint32_t h = mix(id * 128u + s * 64u + i * 4u + q + 1u);
         a[s][i][q] = DT == SLP_BF16 ? two_bf16(h) : __builtin_bit_cast(uint32_t, one_f32(h));
       }
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const uint32_t h = mix(id * 64u + s * 32u + 16u + j * 4u + q + 1u);
+        const uint32_t h = mix(id * 128u + s * 64u + 32u + j * 4u + q + 1u);
         b[s][j][q] = DT == SLP_BF16 ? two_bf16(h) : __builtin_bit_cast(uint32_t, one_f32(h));
       }
   }
-  for (int it = 0; it < iters; ++it) {
+  float t = 0.0f;
+  if constexpr (DT == SLP_BF16) {
+    f32x4 acc[NA * NB];
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int i = 0; i < NA * NB; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int r = 0; r < 4; ++r) acc[i][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          if (DT == SLP_BF16) {
-            acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[s][i]),
-                                                                     __builtin_bit_cast(bf16x8, b[s][j]), acc[i * 2 + j], 0, 0, 0);
-          } else {
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+          for (int j = 0; j < NB; ++j)
+            acc[i * NB + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[s][i]),
+                                                                      __builtin_bit_cast(bf16x8, b[s][j]), acc[i * NB + j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < NA * NB; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) t += acc[i][r];
+  } else {
+    f32x16 acc[NA * NB];
+#pragma unroll
+    for (int i = 0; i < NA * NB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+          for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-              acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a[s][i][q]),
-                                                                    __builtin_bit_cast(float, b[s][j][q]), acc[i * 2 + j], 0, 0, 0);
-          }
-        }
+              acc[i * NB + j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a[s][i][q]),
+                                                                     __builtin_bit_cast(float, b[s][j][q]), acc[i * NB + j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < NA * NB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t += acc[i][r];
   }
-  float t = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) t += acc[i][r];
   sink[id] = t;
 }
 
@@ -88,8 +109,8 @@ __global__ __launch_bounds__(512) void mfma_issue_kernel(int iters, float* sink)
 // Launches the probe on `grid` workgroups of 512 threads; sink must hold grid*512 floats.
 // flops_per_workgroup_iter: algorithmic FLOPs one workgroup issues per loop iteration.
 hipError_t launch_mfma_probe(int dtype, int iters, int grid, float* sink, double* flops_per_workgroup_iter, hipStream_t s) {
-  // 8 wavefronts x 16 MFMA groups per iteration; a bf16 32x32x16 MFMA is 2*32*32*16 FLOPs, the float32 group is four 32x32x2
-  *flops_per_workgroup_iter = 8.0 * 16.0 * (dtype == SLP_BF16 ? 2.0 * 32 * 32 * 16 : 4 * 2.0 * 32 * 32 * 2);
+  // 8 wavefronts x (bf16: 64 MFMAs of 2*16*16*32 FLOPs; float32: 16 groups of four 32x32x2) per iteration
+  *flops_per_workgroup_iter = 8.0 * (dtype == SLP_BF16 ? 64 * 2.0 * 16 * 16 * 32 : 16 * 4 * 2.0 * 32 * 32 * 2);
   if (dtype == SLP_BF16) hipLaunchKernelGGL(mfma_issue_kernel<SLP_BF16>, dim3(grid), dim3(512), 0, s, iters, sink);
   else hipLaunchKernelGGL(mfma_issue_kernel<SLP_F32>, dim3(grid), dim3(512), 0, s, iters, sink);
   return hipGetLastError();
