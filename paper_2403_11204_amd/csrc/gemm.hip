@@ -40,6 +40,8 @@
 //   * workgroup -> tile: consecutive workgroup ids go round-robin over the 8 XCDs, so
 //     ids are first regrouped per XCD (each XCD gets a contiguous range of tiles and
 //     its own 4 MB L2 sees a compact set of operand rows), then walked in column-major groups of 8 tile-rows.
+//     Big products whose tile grid divides into 16 x 16 regions are walked region by region instead, all 8 XCDs
+//     inside one region at a time (see the kernel).
 #include "slp_kernels.h"
 
 namespace slp {

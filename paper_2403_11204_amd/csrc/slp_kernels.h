@@ -33,7 +33,7 @@ struct GemmArgs {
   const void* B;   // [N][ldb]
   int lda, ldb;
   int M, N, K;     // logical sizes; pads up to the next chunk must be zero in A and B
-  int group_m;     // tile rows per group of the workgroup -> tile walk; 0 = default (set by launch_gemm)
+  int group_m;     // tile rows per group of the workgroup -> tile walk; 0 = default, -1 = 16 x 16 regions (set by launch_gemm)
   // EPI_FWD  : v = acc + bias[n], optional ReLU; C (row-major) and/or CT (transposed) in T
   // EPI_DGRAD: v = acc * [maskT[n][m] > 0];      C and/or CT in T
   // EPI_WGRAD: Cf[m][n] = acc (float32)
