@@ -335,6 +335,16 @@ def test_seeded_random_shapes(seed):
     check_step(g, o, X, y, table, dtype, steps=2)
 
 
+@pytest.mark.parametrize("widths,B", [([4000, 4090, 3999], 3900), ([4000, 4400, 4100], 3900)], ids=["regions", "groups"])
+def test_bf16_products_on_the_big_tile_with_ragged_edges(widths, B):
+    # every product of these steps has 224 or more 256x256 tiles, so all run through the big bf16 kernel, with ragged
+    # last tiles in rows, columns and contraction: 16 x 16 tile grids (walked by regions) in the first case, 16 x 18
+    # and 18 x 17 grids (walked by groups of tile rows) in the second
+    X, y, table = case_data(widths, api.MSE_SIL, B, api.NORMAL, 29, seed=12)
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, api.BF16, max_batch=B, lr=0.05, mom=0.9, wseed=13)
+    check_step(g, o, X, y, table, api.BF16)
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_seeded_random_mid_size_shapes(seed):
     # ragged sizes large enough to reach the 64x64, 128x128 (both forms) and 256x256 tile instantiations
