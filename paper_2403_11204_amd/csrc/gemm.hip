@@ -37,6 +37,7 @@
 //     is one vector store into the transposed output; for the row-major output the quad of lanes holding
 //     4 adjacent columns transposes its 4x4 block with DPP moves, after which a lane holds 4 consecutive
 //     columns of one row: one vector store as well (2 stores per quad instead of 5).
+//     The big kernel's bf16 outputs go through LDS instead and leave as whole 512-byte rows (see its epilogue).
 //   * workgroup -> tile: consecutive workgroup ids go round-robin over the 8 XCDs, so
 //     ids are first regrouped per XCD (each XCD gets a contiguous range of tiles and
 //     its own 4 MB L2 sees a compact set of operand rows), then walked in column-major groups of 8 tile-rows.
@@ -525,18 +526,98 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
 #undef SLP_BARRIER
 #undef VMCNT
 
+  if constexpr (EPI == EPI_WGRAD) {
 #pragma unroll
-  for (int j = 0; j < NB; ++j) {
-    const int n = n0 + wn * WTN + j * 16 + lrow;
-    float bias = 0.0f;
-    if (EPI == EPI_FWD && n < g.N) bias = g.bias[n];
+    for (int j = 0; j < NB; ++j) {
+      const int n = n0 + wn * WTN + j * 16 + lrow;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float v[4];
+      for (int i = 0; i < 8; ++i) {
+        float v[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e];
-      store_quad<T, EPI>(g, n, m0 + wm * 128 + i * 16 + 4 * lgrp, bias, v, lane);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e];
+        store_quad<T, EPI>(g, n, m0 + wm * 128 + i * 16 + 4 * lgrp, 0.0f, v, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  } else {
+    // Forward / data gradient: both outputs are bf16, and an accumulator block holds only 32 contiguous bytes of an
+    // output row (or column).  The finished tile therefore goes through LDS (free now: 256 rows x 512 bytes = the two
+    // stages), once transposed and once row-major, and leaves it as whole 512-byte rows in 16-byte pieces per lane.
+    // Chunk c (16 bytes) of LDS row r sits at physical chunk c ^ (r & 31): the 8-byte writes of a wavefront (16 rows
+    // x 2 chunk halves per half-wavefront) and its 16-byte reads (all chunks of a row) are then free of bank conflicts.
+    typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+    __syncthreads();   // every wavefront's (zero-fill) loads have landed and its fragment reads are over
+    // finish the values in place: bias + ReLU / mask, zeros outside the matrix
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int n = n0 + wn * WTN + j * 16 + lrow;
+      const bool col_ok = n < g.N;
+      float bias = 0.0f;
+      if (EPI == EPI_FWD && col_ok) bias = g.bias[n];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int mb = m0 + wm * 128 + i * 16 + 4 * lgrp;
+        if (EPI == EPI_FWD) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[i][j][e] += bias;
+            if (g.relu) acc[i][j][e] = fmaxf(acc[i][j][e], 0.0f);
+          }
+        } else if (g.maskT && col_ok && mb < ((g.M + 7) & ~7)) {
+          const bf16x4 mk = *(const bf16x4*)((const bf16*)g.maskT + (size_t)n * g.ldmask + mb);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (!((float)mk[e] > 0.0f)) acc[i][j][e] = 0.0f;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (mb + e >= g.M || !col_ok) acc[i][j][e] = 0.0f;
+      }
+    }
+    auto pack4 = [](float a, float b, float c, float d) {
+      const bf16x4 o = {(bf16)a, (bf16)b, (bf16)c, (bf16)d};
+      return __builtin_bit_cast(u32x2, o);
+    };
+    // rows [32 w, 32 w + 32) of the staged tile leave through wavefront w: two rows per 16-byte store instruction
+    auto drain = [&](bf16* out, int ld, int row0, int rows_end, int col0, int cols_end) {
+#pragma unroll 4
+      for (int it = 0; it < 16; ++it) {
+        const int r = w * 32 + 2 * it + (lane >> 5), c = lane & 31;
+        const u32x4 val = *(const u32x4*)(smem + r * 512 + ((c ^ (r & 31)) << 4));
+        if (row0 + r < rows_end && col0 + c * 8 < cols_end) *(u32x4*)(out + (size_t)(row0 + r) * ld + col0 + c * 8) = val;
+      }
+    };
+    if (g.CT) {   // transposed: LDS row = output column n, 4 consecutive rows m per lane and block
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int r = wn * WTN + j * 16 + lrow;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int mloc = wm * 128 + i * 16 + 4 * lgrp;     // 8 bytes at element mloc of the row
+          *(u32x2*)(smem + r * 512 + (((mloc >> 3) ^ (r & 31)) << 4) + (mloc & 4) * 2) =
+              pack4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+        }
+      }
+      __syncthreads();
+      drain((bf16*)g.CT, g.ldct, n0, g.N, m0, (g.M + 7) & ~7);
+      if (g.C) __syncthreads();
+    }
+    if (g.C) {    // row-major: after the 4x4 transpose inside lane quads a lane holds 4 consecutive columns of one row
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e];
+          quad_transpose(v, lane);
+          const int r = wm * 128 + i * 16 + 4 * lgrp + (lane & 3);
+          const int nloc = wn * WTN + j * 16 + (lrow & ~3);
+          *(u32x2*)(smem + r * 512 + (((nloc >> 3) ^ (r & 31)) << 4) + (nloc & 4) * 2) = pack4(v[0], v[1], v[2], v[3]);
+        }
+      }
+      __syncthreads();
+      drain((bf16*)g.C, g.ldc, m0, g.M, n0, g.N);
     }
   }
 #endif
@@ -789,6 +870,10 @@ hipError_t launch_gemm(int dtype, int epi, const GemmArgs& g, hipStream_t s) {
   if (epi == EPI_FWD && !g.bias) return hipErrorInvalidValue;
   if (epi == EPI_WGRAD && !g.Cf) return hipErrorInvalidValue;
   if (epi != EPI_WGRAD && !g.C && !g.CT) return hipErrorInvalidValue;
+  // outputs are written as 16-byte vectors
+  if (epi != EPI_WGRAD && ((g.C && (g.ldc % kLdAlign || ((uintptr_t)g.C & 15))) || (g.CT && (g.ldct % kLdAlign || ((uintptr_t)g.CT & 15)))))
+    return hipErrorInvalidValue;
+  if (epi == EPI_WGRAD && (g.ldc % 4 || ((uintptr_t)g.Cf & 15))) return hipErrorInvalidValue;
   const int cfg = pick_cfg(g.M, g.N);
   GemmArgs h = g;
   // Height of the tile groups each XCD walks (the 32 tiles an XCD runs together are group_m tile rows x 32/group_m
