@@ -87,6 +87,8 @@ def build_segments(cfg, n_batches):
         seg.init(100 + si)
         if cfg.get("graph"):        # launch-bound sizes: replay the captured launch sequence of a step
             seg.set_graph(True)
+        if cfg.get("overlap"):      # segments stepped one after another: the update tail of one runs beside the next
+            seg.set_overlap(True)
         if si == 0:
             inputs.append(X0)
         else:   # an interior/final segment sees the previous cut's label of the class plus noise (sigma 0.05)
@@ -130,6 +132,8 @@ def time_workload(segs, inputs, ys, use_streams, steps, warmup, profile=True):
     if streams:
         for st in streams:
             cur.wait_stream(st)
+    for s in segs:
+        s.join()              # updates that the last steps left running (overlap on) belong to the timed region
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -183,6 +187,8 @@ def main():
                     help="first run one plain 1 GiB -> 1 GiB elementwise copy kernel (scale reference for HBM byte counters)")
     ap.add_argument("--eager", action="store_true", help="configs 0-2: launch every kernel of a step instead of replaying graphs")
     ap.add_argument("--serial", action="store_true", help="config 3: run the four segments one after another on one stream")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="end every step by waiting for its parameter updates (slp_segment_set_overlap off)")
     ap.add_argument("--concurrent", action="store_true", help="run the segments at the same time on a stream each (the default of config 3)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -194,6 +200,7 @@ def main():
         cfg["streams"] = False
     if args.concurrent:
         cfg["streams"] = True
+    cfg["overlap"] = len(cfg["segs"]) > 1 and not cfg["streams"] and not cfg.get("graph") and not args.no_overlap
     big = args.config in (3, 4)
     steps = args.steps if args.steps is not None else (20 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
@@ -234,7 +241,8 @@ def main():
         "config": {"workload": cfg["name"], "global_batch": B, "classes": cfg["classes"],
                    "segments": [s[0] for s in cfg["segs"]], "optimizer": "sgd lr %g momentum %g" % (cfg["lr"], cfg["mom"]),
                    "concurrent_streams": len(segs) if cfg["streams"] else 1,
-                   "launch": "hip graph replay" if cfg.get("graph") and not args.eager else "eager"},
+                   "launch": "hip graph replay" if cfg.get("graph") and not args.eager else "eager",
+                   "update_overlap": bool(cfg["overlap"])},
         "step_tflops": flops_step / (ms * 1e-3) / 1e12,
         "step_frac_of_mfma_peak": flops_step / (ms * 1e-3) / 1e12 / peak,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,

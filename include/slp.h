@@ -204,6 +204,20 @@ int slp_segment_step_external(slp_segment* seg, const void* X /*device*/, const 
  * and step on that to have a single combination).  Off by default. */
 int slp_segment_set_graph(slp_segment* seg, int on);
 
+/* ---- several segments trained side by side (end of Sec. 2: partitions are independent jobs) ----
+ * The last thing a step does is stream every parameter once (the SGD update); it runs on a stream of the handle
+ * beside the matrix products that are still to come, and the step normally ends by making `stream` wait for it.
+ * With overlap on, slp_segment_step (and slp_segment_step_external) returns without that wait, and the update of
+ * the first layer moves to the side stream too: whatever the caller enqueues next on `stream` -- typically the
+ * step of another segment -- runs beside the tail of this one.  Every later call on the handle that takes a stream
+ * first makes that stream wait for the pending updates, so calls through this interface see the same values as
+ * without overlap (bit for bit).  A caller that reads or frees the parameter or workspace buffers directly must
+ * call slp_segment_join first (slp_segment_destroy and slp_segment_bind wait on the host).  No effect on steps that
+ * are captured into a graph.  Off by default.
+ * slp_segment_join: makes `stream` wait for updates a previous step left running; a no-op when none are pending. */
+int slp_segment_set_overlap(slp_segment* seg, int on);
+int slp_segment_join(slp_segment* seg, slp_stream stream);
+
 /* ---- measurement hooks -------------------------------------------------------------
  * When enabled, every matrix-product launch of the segment is bracketed by HIP
  * events on its stream.  slp_segment_profile_read synchronises the recorded events,

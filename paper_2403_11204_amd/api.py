@@ -64,6 +64,8 @@ def lib():
         "slp_segment_step_external": (i32, [vp, vp, vp, i32, vp]),
         "slp_segment_profile_enable": (i32, [vp, i32]),
         "slp_segment_set_graph": (i32, [vp, i32]),
+        "slp_segment_set_overlap": (i32, [vp, i32]),
+        "slp_segment_join": (i32, [vp, vp]),
         "slp_segment_profile_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]),
         "slp_probe_mfma_rate": (i32, [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]),
     }
@@ -80,7 +82,7 @@ EXPORTS = ["slp_last_error", "slp_make_synthetic_labels", "slp_make_segment_inpu
            "slp_segment_get_momentum", "slp_segment_get_activation", "slp_segment_set_lr", "slp_segment_set_labels",
            "slp_segment_step", "slp_segment_forward", "slp_segment_input_grad", "slp_segment_step_external",
            "slp_segment_profile_enable", "slp_segment_profile_read", "slp_probe_mfma_rate",
-           "slp_segment_set_graph"]
+           "slp_segment_set_graph", "slp_segment_set_overlap", "slp_segment_join"]
 
 
 def _check(code):
@@ -222,6 +224,14 @@ class Segment:
     def set_graph(self, on=True):
         """slp_segment_set_graph: replay captured launch sequences of step() (for launch-bound segments)."""
         _check(lib().slp_segment_set_graph(self._h, int(bool(on))))
+
+    def set_overlap(self, on=True):
+        """slp_segment_set_overlap: step() returns with the parameter updates still running beside the caller's next work."""
+        _check(lib().slp_segment_set_overlap(self._h, int(bool(on))))
+
+    def join(self):
+        """slp_segment_join: the current stream waits for updates a step with overlap on left running."""
+        _check(lib().slp_segment_join(self._h, _stream()))
 
     def profile_read(self):
         ms, n, fl = ctypes.c_double(), ctypes.c_int64(), ctypes.c_double()

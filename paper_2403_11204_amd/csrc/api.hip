@@ -91,6 +91,10 @@ struct slp_segment {
   hipStream_t side;
   std::vector<hipEvent_t> ev_fork;   // one per layer
   hipEvent_t ev_join;
+  // slp_segment_set_overlap: every layer's update goes to the side stream and slp_segment_step leaves the join to the
+  // handle's next call that takes a stream (settle), so that the optimiser tail of one segment runs beside whatever
+  // the caller enqueues next -- typically the step of another segment.
+  bool defer_join, join_pending;
   // Small segments are bound by launch latency, not by the GPU: with graphs on, the launch sequence of a step
   // is captured once per (X, targets, batch, loss_out) and replayed as one graph launch afterwards.
   bool use_graph, graph_warm;
@@ -205,7 +209,23 @@ int data_gradient(slp_segment* seg, int l, int batch, hipStream_t st) {
 }
 
 // backward + update, last layer first; the data gradient of layer l reads W_l before it is updated
+// Makes `st` wait for updates a previous step left running on the side stream (deferred join).
+int settle(slp_segment* seg, hipStream_t st) {
+  if (seg->join_pending) {
+    HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
+    seg->join_pending = false;
+  }
+  return SLP_OK;
+}
+
+// Weight updates of large layers that run on the side stream, beside the next matrix products, are held to one workgroup
+// per compute unit (256, 512 and 128 were tried: 256 is best, -2 % per step on the comparison and deep configurations).
+constexpr int kSideUpdateWorkgroups = 256;
 int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
+  // a join cannot be left to a later call while the launches are being captured into a graph
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (seg->defer_join && st) HIP_TRY(hipStreamIsCapturing(st, &cap));
+  const bool defer = seg->defer_join && cap == hipStreamCaptureStatusNone;
   for (int l = seg->L; l >= 1; --l) {
     Layer& ly = seg->layers[l - 1];
     if (l > 1) {
@@ -221,7 +241,8 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
     if (rc) return rc;
     // fork: everything layer l still needs (bias gradient, both updates) reads dZ_l^T / dW_l, which are
     // complete here, and writes only layer l's parameters, which nothing below reads in this step
-    hipStream_t us = l > 1 ? seg->side : st;      // the last layer has nothing left to overlap with
+    // without a deferred join the first layer has nothing left in this step to overlap with
+    hipStream_t us = (l > 1 || defer) ? seg->side : st;
     if (us != st) {
       HIP_TRY(hipEventRecord(seg->ev_fork[l - 1], st));
       HIP_TRY(hipStreamWaitEvent(us, seg->ev_fork[l - 1], 0));
@@ -230,17 +251,18 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
     // of its own first: inside one launch its long reads of dZ^T slowed the matrix products beside it (measured 1 %).
     if ((size_t)ly.N * ly.K <= ((size_t)1 << 22)) {
       HIP_TRY(launch_layer_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->dZT[l],
-                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, us));
+                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, us));
     } else {
       HIP_TRY(launch_layer_update(seg->dtype, nullptr, nullptr, nullptr, ly.N, 0, ly.ldk, nullptr, nullptr, ly.ldn, seg->dZT[l],
-                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, us));
+                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, us));
       HIP_TRY(launch_layer_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, nullptr, 0, 0,
-                                  nullptr, nullptr, nullptr, seg->lr, seg->mu, 0, us));
+                                  nullptr, nullptr, nullptr, seg->lr, seg->mu, 0, us != st ? kSideUpdateWorkgroups : 0, us));
     }
   }
-  if (seg->L > 1) {     // join: later work on the caller's stream sees every update
+  if (seg->L > 1 || defer) {     // join: later work on the caller's stream sees every update
     HIP_TRY(hipEventRecord(seg->ev_join, seg->side));
-    HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
+    if (defer) seg->join_pending = true;
+    else HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
   }
   return SLP_OK;
 }
@@ -249,7 +271,7 @@ int refresh_copies(slp_segment* s, int layer, hipStream_t st) {
   Layer& ly = s->layers[layer];
   if (!ly.W16 && !ly.WT) return SLP_OK;
   HIP_TRY(launch_layer_update(s->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, nullptr, 0, 0, nullptr,
-                              nullptr, nullptr, 0.0f, 0.0f, 1, st));
+                              nullptr, nullptr, 0.0f, 0.0f, 1, 0, st));
   return SLP_OK;
 }
 
@@ -266,6 +288,8 @@ int exchange(slp_segment* s, int layer, float* W, float* b, int which, bool set,
   int rc = check_seg(s, true, !set);
   if (rc) return rc;
   if (layer < 0 || layer >= s->L) return fail(SLP_ERR_ARG, "layer %d out of range [0,%d)", layer, s->L);
+  rc = settle(s, st);
+  if (rc) return rc;
   Layer& ly = s->layers[layer];
   float* mats[3] = {ly.W32, ly.dW, ly.vW};
   float* vecs[3] = {ly.b, ly.db, ly.vb};
@@ -382,6 +406,7 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
   s->work_bytes = off;
 
   s->side = nullptr; s->ev_join = nullptr;
+  s->defer_join = false; s->join_pending = false;
   s->bound = false; s->have_params = false; s->table = nullptr; s->classes = 0; s->last_batch = 0; s->prof = false;
   s->use_graph = false; s->graph_warm = false; s->graph_tick = 0; s->graph_misses = 0;
   s->partials = nullptr; s->loss_dev = nullptr;
@@ -396,7 +421,10 @@ void slp_segment_destroy(slp_segment* seg) {
   for (auto e : seg->ev_fork) (void)hipEventDestroy(e);
   if (seg->ev_join) (void)hipEventDestroy(seg->ev_join);
   drop_graphs(seg);
-  if (seg->side) (void)hipStreamDestroy(seg->side);
+  if (seg->side) {
+    (void)hipStreamSynchronize(seg->side);   // updates of a step with a deferred join may still be writing the caller's buffers
+    (void)hipStreamDestroy(seg->side);
+  }
   delete seg;
 }
 
@@ -407,6 +435,10 @@ int slp_segment_bind(slp_segment* seg, void* params, size_t params_bytes, void* 
                      slp_stream stream) {
   int rc = check_seg(seg, false, false);
   if (rc) return rc;
+  if (seg->join_pending) {     // the old buffers are still being written
+    HIP_TRY(hipStreamSynchronize(seg->side));
+    seg->join_pending = false;
+  }
   if (!params || !workspace) return fail(SLP_ERR_ARG, "params and workspace must not be NULL");
   if (((uintptr_t)params | (uintptr_t)workspace) & (kAlign - 1)) return fail(SLP_ERR_ALLOC, "buffers must be 256-byte aligned");
   if (params_bytes < seg->param_bytes) return fail(SLP_ERR_ALLOC, "params buffer has %zu bytes, %zu needed", params_bytes, seg->param_bytes);
@@ -451,6 +483,8 @@ int slp_segment_init(slp_segment* seg, uint64_t seed, slp_stream stream) {
   int rc = check_seg(seg, true, false);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
+  rc = settle(seg, st);
+  if (rc) return rc;
   for (int l = 0; l < seg->L; ++l) {
     Layer& ly = seg->layers[l];
     HIP_TRY(launch_init_weights(seed, l, ly.W32, ly.N, ly.K, ly.ldk, ly.b, st));
@@ -485,6 +519,8 @@ int slp_segment_get_activation(slp_segment* seg, int layer, int kind, int batch,
   if (layer < 0 || layer > seg->L || (kind != 0 && kind != 1)) return fail(SLP_ERR_ARG, "layer %d / kind %d out of range", layer, kind);
   if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
   hipStream_t st = (hipStream_t)stream;
+  rc = settle(seg, st);
+  if (rc) return rc;
   const int w = seg->widths[layer];
   if (kind == 0) {
     HIP_TRY(launch_copy_transpose(seg->dtype, seg->A[layer], seg->ldw[layer], batch, w, out, w, nullptr, 0, 0, nullptr, 0, st));
@@ -550,6 +586,8 @@ int slp_segment_step(slp_segment* seg, const void* X, const int32_t* targets, in
   if (seg->loss == SLP_MSE_SIL && !seg->table) return fail(SLP_ERR_STATE, "no label table bound: call slp_segment_set_labels first");
   hipStream_t st = (hipStream_t)stream;
   seg->last_batch = batch;
+  rc = settle(seg, st);
+  if (rc) return rc;
 
   auto launch_all = [&]() -> int {
     int r = ingest(seg, X, batch, true, st);
@@ -617,6 +655,19 @@ int slp_segment_set_graph(slp_segment* seg, int on) {
   return SLP_OK;
 }
 
+int slp_segment_set_overlap(slp_segment* seg, int on) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  seg->defer_join = on != 0;
+  return SLP_OK;
+}
+
+int slp_segment_join(slp_segment* seg, slp_stream stream) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  return settle(seg, (hipStream_t)stream);
+}
+
 int slp_segment_input_grad(slp_segment* seg, const void* X, const int32_t* targets, int batch, void* dX, float* loss_out,
                            slp_stream stream) {
   int rc = check_seg(seg, true, true);
@@ -626,6 +677,8 @@ int slp_segment_input_grad(slp_segment* seg, const void* X, const int32_t* targe
   if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
   if (seg->loss == SLP_MSE_SIL && !seg->table) return fail(SLP_ERR_STATE, "no label table bound: call slp_segment_set_labels first");
   hipStream_t st = (hipStream_t)stream;
+  rc = settle(seg, st);
+  if (rc) return rc;
   rc = ingest(seg, X, batch, true, st);
   if (rc) return rc;
   rc = forward_layers(seg, batch, true, st);
@@ -648,6 +701,8 @@ int slp_segment_step_external(slp_segment* seg, const void* X, const void* dA_ou
   if (!X || !dA_out) return fail(SLP_ERR_ARG, "X and dA_out must not be NULL");
   if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
   hipStream_t st = (hipStream_t)stream;
+  rc = settle(seg, st);
+  if (rc) return rc;
   const int L = seg->L, D = seg->widths[L];
   rc = ingest(seg, X, batch, true, st);
   if (rc) return rc;

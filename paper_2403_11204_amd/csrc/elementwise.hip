@@ -352,7 +352,7 @@ __device__ __forceinline__ void sgd_update_block(int bx, int by, float* __restri
 #pragma unroll
     for (int e = 0; e < 4; ++e) tile[rr][q * 4 + e] = from_f32<T>(w[p][e]);
   }
-  if (!WT) return;
+  if (!WT) return;      // (uniform over the launch)
   __syncthreads();
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
@@ -381,6 +381,22 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32
                                                          bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
                                                          float mu, int refresh_only) {
   sgd_update_block<T>(blockIdx.x, blockIdx.y, W32, vW, dW, N, K, ldk, W16, WT, ldn, lr, mu, refresh_only);
+}
+
+// The same on a fixed number of workgroups that walk the tiles with the grid's stride: for updates that run beside
+// matrix products.  At full width the update saturates HBM and the product next to it, which waits on every load,
+// all but stops (measured: a 1.3 ms update stretched the product beside it from 3.15 to 4.29 ms); one workgroup per
+// compute unit takes longer over the same bytes and costs the product less.
+template <typename T>
+__global__ __launch_bounds__(256) void sgd_update_strided_kernel(float* __restrict__ W32, float* __restrict__ vW,
+                                                                 const float* __restrict__ dW, int N, int K, int ldk,
+                                                                 bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
+                                                                 float mu, int refresh_only) {
+  const int kb = (K + 63) / 64, tiles = kb * ((N + 63) / 64);
+  for (int id = blockIdx.x; id < tiles; id += gridDim.x) {
+    sgd_update_block<T>(id % kb, id / kb, W32, vW, dW, N, K, ldk, W16, WT, ldn, lr, mu, refresh_only);
+    __syncthreads();   // the LDS tile is reused
+  }
 }
 
 template <typename T>
@@ -455,8 +471,16 @@ hipError_t launch_reduce_loss(const float* partials, int n, double scale, float*
 
 hipError_t launch_layer_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16, void* WT,
                                int ldn, const void* dZT, int ldt, int B, float* db, float* b, float* vb, float lr, float mu,
-                               int refresh_only, hipStream_t s) {
+                               int refresh_only, int max_workgroups, hipStream_t s) {
   if (!dZT) {       // weights only
+    const int wgs = max_workgroups;
+    if (wgs > 0 && (long)((K + 63) / 64) * ((N + 63) / 64) > wgs) {
+      if (dtype == 1)
+        sgd_update_strided_kernel<bf16><<<wgs, 256, 0, s>>>(W32, vW, dW, N, K, ldk, (bf16*)W16, (bf16*)WT, ldn, lr, mu, refresh_only);
+      else
+        sgd_update_strided_kernel<float><<<wgs, 256, 0, s>>>(W32, vW, dW, N, K, ldk, nullptr, (float*)WT, ldn, lr, mu, refresh_only);
+      return hipGetLastError();
+    }
     dim3 grid2((K + 63) / 64, (N + 63) / 64);
     if (dtype == 1)
       sgd_update_kernel<bf16><<<grid2, 256, 0, s>>>(W32, vW, dW, N, K, ldk, (bf16*)W16, (bf16*)WT, ldn, lr, mu, refresh_only);
