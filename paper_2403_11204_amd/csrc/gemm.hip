@@ -578,11 +578,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
       const bf16x4 o = {(bf16)a, (bf16)b, (bf16)c, (bf16)d};
       return __builtin_bit_cast(u32x2, o);
     };
-    // rows [32 w, 32 w + 32) of the staged tile leave through wavefront w: two rows per 16-byte store instruction
+    // rows [256 / NW * w, 256 / NW * (w + 1)) of the staged tile leave through wavefront w: two rows per 16-byte store
+    // instruction
     auto drain = [&](bf16* out, int ld, int row0, int rows_end, int col0, int cols_end) {
 #pragma unroll 4
-      for (int it = 0; it < 16; ++it) {
-        const int r = w * 32 + 2 * it + (lane >> 5), c = lane & 31;
+      for (int it = 0; it < 128 / NW; ++it) {
+        const int r = w * (256 / NW) + 2 * it + (lane >> 5), c = lane & 31;
         const u32x4 val = *(const u32x4*)(smem + r * 512 + ((c ^ (r & 31)) << 4));
         if (row0 + r < rows_end && col0 + c * 8 < cols_end) *(u32x4*)(out + (size_t)(row0 + r) * ld + col0 + c * 8) = val;
       }
