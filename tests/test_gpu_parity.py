@@ -283,6 +283,19 @@ def test_forward_only_and_determinism(dtype):
         assert torch.equal(g.get_params(l)[0], g2.get_params(l)[0])
 
 
+def test_forward_only_in_place_through_the_big_kernel():
+    # a stored-response pass at a size that runs the 256x256 bf16 kernel: the caller's input is read in place (width a
+    # multiple of 64) and the result written straight into the caller's buffer by the staged epilogue's 16-byte stores
+    widths, B = [4096, 4096, 3968], 3900
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, api.BF16, max_batch=B, lr=0.01, mom=0.9, wseed=21)
+    X, _, _ = case_data(widths, api.MSE_SIL, B, api.NORMAL, 7, seed=4)
+    Xd, Xv = as_input(X, api.BF16)
+    out = torch.full((B + 1, widths[-1]), 7.0, dtype=torch.bfloat16, device=DEV)     # one guard row behind the result
+    g.forward(Xd, out=out[:B])
+    assert rel_err(to_np(out[:B]), o.forward(Xv)) <= TOL[api.BF16]
+    assert bool((out[B] == 7.0).all())
+
+
 def test_step_argument_errors():
     g, _ = make_pair([16, 8], api.RELU_ALL, api.MSE_SIL, api.F32, 32, 0.01, 0.9, wseed=1)
     X = torch.zeros((64, 16), device=DEV)
