@@ -83,3 +83,30 @@ def test_destroy_right_after_an_overlapped_step():
     # the device is healthy and a fresh handle works
     h = build(widths, api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, api.BF16, B, 7, False)
     assert torch.isfinite(h.step(Xd, yd)).all()
+
+
+def test_recovery_steps_with_overlap_equal_ordinary_ones():
+    # Sec. 5's loop (left forward, right input gradient, left step from that gradient) with overlap on for the left
+    # partition: step_external leaves its updates running, the next forward on the handle waits for them
+    B, classes = 256, 9
+    wl, wr = [80, 2304, 2100, 64], [64, 96, classes]
+    states = []
+    for overlap in (False, True):
+        left = build(wl, api.RELU_ALL, api.MSE_SIL, api.F32, B, 3, overlap)
+        right = api.Segment(wr, api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, max_batch=B, dtype=api.F32, lr=0.05,
+                            momentum=0.9, input_grad=True)
+        for l, (W, b) in enumerate(datagen.uniform_weights(wr, 4)):
+            right.set_params(l, torch.from_numpy(W), torch.from_numpy(b))
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(stream):
+            for it in range(4):
+                X, y = datagen.class_mean_inputs(B, classes, dim=wl[0], seed=5, first=it * B)
+                Xd, yd = torch.from_numpy(X).to(DEV), torch.from_numpy(y).to(DEV)
+                resp = left.forward(Xd)
+                d_resp, _ = right.input_grad(resp, yd)
+                left.step_external(Xd, d_resp)
+            states.append([left.get_params(l)[0].clone() for l in range(left.L)])
+        stream.synchronize()
+    for a, b in zip(*states):
+        assert torch.equal(a, b)
