@@ -482,8 +482,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
                                {10, 0}, {11, 0}, {12, 0}, {15, 0}, {2, 0}, {3, 0}, {4, 0}, {16, 0}};
   constexpr Slot kNarrow4[16] = {{1, 0}, {0, 0}, {13, 0}, {0, 0}, {2, 0}, {0, 0}, {14, 0}, {0, 0},
                                  {3, 0}, {0, 0}, {15, 0}, {0, 0}, {4, 0}, {0, 0}, {16, 0}, {0, 0}};
-  constexpr Slot kWide8[8] = {{1, 5}, {6, 0}, {13, 0}, {7, 0}, {8, 2}, {14, 0}, {3, 0}, {4, 0}};
-  constexpr Slot kNarrow8[8] = {{1, 0}, {13, 0}, {2, 0}, {0, 0}, {3, 0}, {14, 0}, {4, 0}, {0, 0}};
+  // 8 wavefronts: the reads go first (they have then returned when the unit ends in a barrier: +1 % over reads
+  // spread through the unit), the loads after them
+  constexpr Slot kWide8[8] = {{1, 5}, {6, 7}, {8, 2}, {3, 4}, {13, 0}, {0, 0}, {14, 0}, {0, 0}};
+  constexpr Slot kNarrow8[8] = {{1, 2}, {3, 4}, {13, 0}, {0, 0}, {0, 0}, {14, 0}, {0, 0}, {0, 0}};
   // one unit: fragments of (h, kk) from af[buf], bfr[kk]; reads for the next unit (A fragments of (rh, rk) into
   // af[buf ^ 1], and, in a wide unit, the B fragments of sub-step rk) from stage rs; loads lbase.. of tile lkt into stage ls
   auto unit = [&](bool wide, int h, int kk, int buf, int rs, int rh, int rk, int lkt, int ls, int lbase) {
