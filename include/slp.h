@@ -209,11 +209,13 @@ int slp_segment_set_graph(slp_segment* seg, int on);
  * beside the matrix products that are still to come, and the step normally ends by making `stream` wait for it.
  * With overlap on, slp_segment_step (and slp_segment_step_external) returns without that wait, and the update of
  * the first layer moves to the side stream too: whatever the caller enqueues next on `stream` -- typically the
- * step of another segment -- runs beside the tail of this one.  Every later call on the handle that takes a stream
- * first makes that stream wait for the pending updates, so calls through this interface see the same values as
- * without overlap (bit for bit).  A caller that reads or frees the parameter or workspace buffers directly must
- * call slp_segment_join first (slp_segment_destroy and slp_segment_bind wait on the host).  No effect on steps that
- * are captured into a graph.  Off by default.
+ * step of another segment -- runs beside the tail of this one.  Until the handle's next step, every call on the
+ * handle that takes a stream first makes that stream wait for the pending updates (whichever stream it is), so calls
+ * through this interface see the same values as without overlap (bit for bit).  A caller that reads or frees the
+ * parameter or workspace buffers directly must call slp_segment_join first (slp_segment_destroy and slp_segment_bind
+ * wait on the host).  No effect on steps that are captured into a graph; a stream that is being captured cannot wait
+ * for updates left pending outside the capture: such a call fails with SLP_ERR_STATE.  Turning overlap off waits on
+ * the host for pending updates, after which the handle is back to plain stream order.  Off by default.
  * slp_segment_join: makes `stream` wait for updates a previous step left running; a no-op when none are pending. */
 int slp_segment_set_overlap(slp_segment* seg, int on);
 int slp_segment_join(slp_segment* seg, slp_stream stream);

@@ -209,12 +209,19 @@ int data_gradient(slp_segment* seg, int l, int batch, hipStream_t st) {
 }
 
 // backward + update, last layer first; the data gradient of layer l reads W_l before it is updated
-// Makes `st` wait for updates a previous step left running on the side stream (deferred join).
+// Makes `st` wait for updates a previous step left running on the side stream (deferred join).  The flag stays set
+// until the next step replaces the event (or the host has waited): every stream that touches the handle in between
+// gets the wait, not only the first one.
 int settle(slp_segment* seg, hipStream_t st) {
-  if (seg->join_pending) {
-    HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
-    seg->join_pending = false;
+  if (!seg->join_pending) return SLP_OK;
+  if (st) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    HIP_TRY(hipStreamIsCapturing(st, &cap));
+    if (cap != hipStreamCaptureStatusNone)
+      return fail(SLP_ERR_STATE, "updates of an overlapped step are still pending and a stream that is being captured cannot "
+                                 "wait for them: call slp_segment_set_overlap(seg, 0) before the capture");
   }
+  HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
   return SLP_OK;
 }
 
@@ -261,9 +268,9 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
   }
   if (seg->L > 1 || defer) {     // join: later work on the caller's stream sees every update
     HIP_TRY(hipEventRecord(seg->ev_join, seg->side));
-    if (defer) seg->join_pending = true;
-    else HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
+    if (!defer) HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
   }
+  seg->join_pending = defer;
   return SLP_OK;
 }
 
@@ -561,6 +568,8 @@ int slp_segment_forward(slp_segment* seg, const void* X, int batch, void* out, s
   if (!X || !out) return fail(SLP_ERR_ARG, "X and out must not be NULL");
   if (batch <= 0 || batch > seg->max_batch) return fail(SLP_ERR_SHAPE, "batch %d not in [1,%d]", batch, seg->max_batch);
   hipStream_t st = (hipStream_t)stream;
+  rc = settle(seg, st);
+  if (rc) return rc;
   // the stored-response pass over a whole dataset (Sec. 2) is this call in a loop: no activation is kept for a
   // backward pass, and dense caller buffers whose rows start on 16-byte boundaries are used in place
   const int w0 = seg->widths[0], w = seg->widths[seg->L];
@@ -659,6 +668,10 @@ int slp_segment_set_overlap(slp_segment* seg, int on) {
   int rc = check_seg(seg, false, false);
   if (rc) return rc;
   seg->defer_join = on != 0;
+  if (!on && seg->join_pending) {      // back to ordinary stream order: nothing is left running
+    HIP_TRY(hipStreamSynchronize(seg->side));
+    seg->join_pending = false;
+  }
   return SLP_OK;
 }
 

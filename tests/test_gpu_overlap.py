@@ -110,3 +110,64 @@ def test_recovery_steps_with_overlap_equal_ordinary_ones():
         stream.synchronize()
     for a, b in zip(*states):
         assert torch.equal(a, b)
+
+
+def test_a_second_stream_between_overlapped_steps():
+    # step on stream A with the join deferred, read the parameters on stream B (ordered after A by the caller), step on
+    # A again: both streams have to wait for the pending updates, not only the first that touches the handle
+    B, classes = 256, 10
+    widths = [64, 2304, 2100, classes]
+    X, y = datagen.class_mean_inputs(B, classes, dim=widths[0], seed=2)
+    Xd = torch.from_numpy(X).to(DEV).to(torch.bfloat16).contiguous()
+    yd = torch.from_numpy(y).to(DEV)
+    finals = []
+    for overlap in (False, True):
+        g = build(widths, api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, api.BF16, B, 7, overlap)
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        sa.wait_stream(torch.cuda.current_stream())
+        reads = []
+        for _ in range(4):
+            with torch.cuda.stream(sa):
+                g.step(Xd, yd)
+            sb.wait_stream(sa)
+            with torch.cuda.stream(sb):
+                reads.append(g.get_params(1)[0].clone())
+            # nothing orders A behind B here: the library's own wait is what keeps the next step behind the updates
+        sa.synchronize(); sb.synchronize()
+        with torch.cuda.stream(sa):
+            g.set_overlap(False)                            # waits on the host; the handle is in plain stream order again
+            reads.append(g.get_params(0)[0].clone())
+        sa.synchronize()
+        finals.append(reads)
+        del g
+    for a, b in zip(*finals):
+        assert torch.equal(a, b)
+
+
+def test_capturing_stream_with_pending_updates_is_refused():
+    B, classes = 128, 10
+    widths = [64, 2304, 2100, classes]
+    g = build(widths, api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, api.BF16, B, 7, True)
+    X, y = datagen.class_mean_inputs(B, classes, dim=widths[0], seed=2)
+    Xd = torch.from_numpy(X).to(DEV).to(torch.bfloat16).contiguous()
+    yd = torch.from_numpy(y).to(DEV)
+    out = torch.empty(B, classes, dtype=torch.bfloat16, device=DEV)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        g.step(Xd, yd)
+        g.step(Xd, yd)                                      # leaves its updates pending
+        graph = torch.cuda.CUDAGraph()
+        with pytest.raises(api.SlpError) as ei:
+            with torch.cuda.graph(graph, stream=stream, capture_error_mode="thread_local"):
+                g.forward(Xd, out=out)
+        assert ei.value.code == -5      # SLP_ERR_STATE
+        g.set_overlap(False)                                # host wait: now the same capture is fine
+        ref = g.forward(Xd).clone()
+        graph2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph2, stream=stream, capture_error_mode="thread_local"):
+            g.forward(Xd, out=out)
+        out.zero_()
+        graph2.replay()
+        stream.synchronize()
+        assert torch.equal(out, ref)
