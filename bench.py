@@ -200,7 +200,8 @@ def main():
         cfg["streams"] = False
     if args.concurrent:
         cfg["streams"] = True
-    cfg["overlap"] = len(cfg["segs"]) > 1 and not cfg["streams"] and not cfg.get("graph") and not args.no_overlap
+    cfg["overlap"] = (len(cfg["segs"]) > 1 and not cfg["streams"] and (not cfg.get("graph") or args.eager)
+                      and not args.no_overlap)
     big = args.config in (3, 4)
     steps = args.steps if args.steps is not None else (20 if big else 200)
     warmup = args.warmup if args.warmup is not None else (3 if big else 20)
