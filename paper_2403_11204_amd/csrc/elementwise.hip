@@ -387,8 +387,12 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32
 // matrix products.  At full width the update saturates HBM and the product next to it, which waits on every load,
 // all but stops (measured: a 1.3 ms update stretched the product beside it from 3.15 to 4.29 ms); one workgroup per
 // compute unit takes longer over the same bytes and costs the product less.
+// Held to 64 registers per lane (8 wavefronts per SIMD): the 256x256 product kernel's two wavefronts per SIMD take 448 of
+// the 512 registers, and a wavefront that needs more than the 64 left cannot share the SIMD with them.  At 68 the
+// update's workgroups could only start on a compute unit between two product workgroups and then kept the next one
+// out for as long as they ran (comparison configuration: 38.9 -> 36.9 ms per step with the limit).
 template <typename T>
-__global__ __launch_bounds__(256) void sgd_update_strided_kernel(float* __restrict__ W32, float* __restrict__ vW,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) void sgd_update_strided_kernel(float* __restrict__ W32, float* __restrict__ vW,
                                                                  const float* __restrict__ dW, int N, int K, int ldk,
                                                                  bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
                                                                  float mu, int refresh_only) {
