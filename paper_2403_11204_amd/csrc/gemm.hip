@@ -363,6 +363,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_kernel(const GemmArgs g) {
 // unit.  Issued in one burst after a single barrier (as gemm_nt_kernel does) they cost the unit that issues them 3x its
 // MFMA time: measured per unit with the cycle counter, 570 / 581 / 498 / 1578 cycles against 512 of MFMAs each.
 // Sustained on 8192x16384x16384: 1295-1315 -> 1365-1415 TFLOP/s.
+// Register budget: 216-222 per lane (allocated as 224), two wavefronts per SIMD; the 64 that remain of the SIMD's 512
+// are what the weight-update kernel running beside the products is held to -- above 224 here it no longer fits.
 template <int EPI, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) {
 #if defined(__HIP_DEVICE_COMPILE__)
