@@ -140,7 +140,8 @@ int slp_segment_get_activation(slp_segment* seg, int layer, int kind, int batch,
 
 int slp_segment_set_lr(slp_segment* seg, float lr, float momentum);
 
-/* Label table for a SLP_MSE_SIL segment: float32 [classes][dim] on the device with
+/* Label table for a SLP_MSE_SIL segment (Sec. 2, first training phase: the left partition is trained against the
+ * synthetic intermediate label of each sample's class): float32 [classes][dim] on the device with
  * dim == the segment's last width; caller-owned, must outlive the steps.
  * Errors: SLP_ERR_STATE (the segment's loss is not SLP_MSE_SIL), SLP_ERR_ARG (null table,
  * classes <= 0), SLP_ERR_SHAPE (dim != last width). */
@@ -187,7 +188,7 @@ int slp_segment_step_external(slp_segment* seg, const void* X /*device*/, const 
                               slp_stream stream);
 
 /* ---- launch-bound segments ----------------------------------------------------------
- * A step of a small segment (the paper's own network is 784-80-60 | 60-60-47, Sec. 3) is a
+ * A step of a small segment (the paper's own network is 784-80-60 | 60-60-60-47, Sec. 3) is a
  * few dozen kernels of a few microseconds each: the host's launch rate, not the GPU, bounds
  * it.  With graphs on, slp_segment_step captures its launch sequence into a HIP graph the
  * first time it sees a combination (X, targets, batch, loss_out) -- the only arguments the
@@ -220,6 +221,23 @@ int slp_segment_set_graph(slp_segment* seg, int on);
 int slp_segment_set_overlap(slp_segment* seg, int on);
 int slp_segment_join(slp_segment* seg, slp_stream stream);
 
+/* ---- the joined network at inference (Sec. 2: the partitions can be joined after training; Sec. 4 reports the
+ * joined network's test accuracy) and the epoch figures of the training curves ----------------------------
+ * slp_count_correct: number of rows n of logits[batch][classes] (dense, row-major, dtype dt, device) whose arg-max
+ * column -- the lowest index among equal maxima -- equals targets[n] (int32, device; an id outside [0, classes) never
+ * matches).  Logits must not be NaN.  The count goes to *correct_out (int64, device): written when accumulate is 0,
+ * added to when it is not (so a loop over the batches of a dataset ends with the dataset's count).  scratch: device
+ * memory of at least 4 * ceil(batch / 4) bytes, 4-byte aligned, caller-owned, overwritten (per-block partial counts;
+ * they are summed in a fixed order, no atomics).  Asynchronous on `stream`.
+ * Errors: SLP_ERR_ARG (null pointer, batch or classes <= 0, unknown dtype), SLP_ERR_ALLOC (scratch too small or
+ * misaligned), SLP_ERR_DEVICE.
+ * slp_mean_loss: *mean_out = (1/n) sum of losses[0..n) (float32, device; summed in float64 in a fixed order): the
+ * epoch mean of the per-step losses that slp_segment_step wrote.  Errors: SLP_ERR_ARG (null, n <= 0), SLP_ERR_DEVICE. */
+int slp_count_correct(const void* logits /*device*/, const int32_t* targets /*device*/, int batch, int classes, int dt,
+                      void* scratch /*device*/, size_t scratch_bytes, int accumulate, int64_t* correct_out /*device*/,
+                      slp_stream stream);
+int slp_mean_loss(const float* losses /*device*/, int n, float* mean_out /*device*/, slp_stream stream);
+
 /* ---- measurement hooks -------------------------------------------------------------
  * When enabled, every matrix-product launch of the segment is bracketed by HIP
  * events on its stream.  slp_segment_profile_read synchronises the recorded events,
@@ -231,7 +249,7 @@ int slp_segment_profile_enable(slp_segment* seg, int on);
 int slp_segment_profile_read(slp_segment* seg, double* gemm_ms, int64_t* gemm_launches, double* gemm_flops);
 
 /* Sustained matrix-pipe rate of the device the caller has made current: a register-only
- * loop of the MFMA instructions the matrix products use (bf16 32x32x16 or float32
+ * loop of the MFMA instructions the matrix products use (bf16 16x16x32 or float32
  * 32x32x2, 8 wavefronts per compute unit, one workgroup per compute unit, pseudo-random
  * operands), `iters` iterations of 16 MFMA groups per wavefront, timed with HIP events
  * on `stream` after a short warm-up launch.  Synchronous.  It is the rate the chip holds

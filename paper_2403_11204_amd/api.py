@@ -68,6 +68,8 @@ def lib():
         "slp_segment_join": (i32, [vp, vp]),
         "slp_segment_profile_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]),
         "slp_probe_mfma_rate": (i32, [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]),
+        "slp_count_correct": (i32, [vp, vp, i32, i32, i32, vp, sz, i32, vp, vp]),
+        "slp_mean_loss": (i32, [vp, i32, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -82,7 +84,7 @@ EXPORTS = ["slp_last_error", "slp_make_synthetic_labels", "slp_make_segment_inpu
            "slp_segment_get_momentum", "slp_segment_get_activation", "slp_segment_set_lr", "slp_segment_set_labels",
            "slp_segment_step", "slp_segment_forward", "slp_segment_input_grad", "slp_segment_step_external",
            "slp_segment_profile_enable", "slp_segment_profile_read", "slp_probe_mfma_rate",
-           "slp_segment_set_graph", "slp_segment_set_overlap", "slp_segment_join"]
+           "slp_segment_set_graph", "slp_segment_set_overlap", "slp_segment_join", "slp_count_correct", "slp_mean_loss"]
 
 
 def _check(code):
@@ -124,6 +126,30 @@ def probe_mfma_rate(dtype=BF16, iters=20000, device="cuda"):
     tf, ms = ctypes.c_double(), ctypes.c_double()
     _check(lib().slp_probe_mfma_rate(dtype, iters, _ptr(scratch), scratch.numel() * 4, ctypes.byref(tf), ctypes.byref(ms), _stream()))
     return tf.value, ms.value
+
+
+def count_correct(logits, targets, out=None, accumulate=False):
+    """slp_count_correct: rows whose arg-max logit is the row's class, as a device int64 scalar (added to `out`
+    when accumulate is set)."""
+    assert logits.is_cuda and logits.is_contiguous() and logits.dim() == 2 and logits.dtype in (torch.float32, torch.bfloat16)
+    assert targets.dtype == torch.int32 and targets.numel() == logits.shape[0]
+    if out is None:
+        assert not accumulate
+        out = torch.empty(1, dtype=torch.int64, device=logits.device)
+    scratch = torch.empty((logits.shape[0] + 3) // 4, dtype=torch.int32, device=logits.device)
+    _check(lib().slp_count_correct(_ptr(logits), _ptr(targets), logits.shape[0], logits.shape[1],
+                                   BF16 if logits.dtype == torch.bfloat16 else F32, _ptr(scratch), scratch.numel() * 4,
+                                   int(bool(accumulate)), _ptr(out), _stream()))
+    return out
+
+
+def mean_loss(losses, out=None):
+    """slp_mean_loss: mean of a contiguous run of float32 device scalars, as a device scalar."""
+    assert losses.is_cuda and losses.is_contiguous() and losses.dtype == torch.float32
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=losses.device)
+    _check(lib().slp_mean_loss(_ptr(losses), losses.numel(), _ptr(out), _stream()))
+    return out
 
 
 class Segment:
@@ -189,13 +215,16 @@ class Segment:
         _check(lib().slp_segment_get_activation(self._h, layer, kind, batch, _ptr(out), _stream()))
         return out
 
-    def step(self, X, targets, want_loss=True):
-        """slp_segment_step; returns the device scalar holding the batch loss."""
+    def step(self, X, targets, want_loss=True, loss_out=None):
+        """slp_segment_step; returns the device scalar holding the batch loss (loss_out, a one-element float32 device
+        tensor such as a slot of a loss curve, or the handle's own scalar)."""
         assert X.is_cuda and X.is_contiguous() and X.dtype == _torch_dtype(self.dtype) and X.shape[1] == self.widths[0]
         assert targets.dtype == torch.int32 and targets.numel() == X.shape[0]
-        _check(lib().slp_segment_step(self._h, _ptr(X), _ptr(targets), X.shape[0], _ptr(self._loss) if want_loss else None,
+        dst = self._loss if loss_out is None else loss_out
+        assert dst.dtype == torch.float32 and dst.numel() == 1 and dst.is_cuda
+        _check(lib().slp_segment_step(self._h, _ptr(X), _ptr(targets), X.shape[0], _ptr(dst) if want_loss else None,
                                       _stream()))
-        return self._loss
+        return dst
 
     def forward(self, X, out=None):
         assert X.is_cuda and X.is_contiguous() and X.dtype == _torch_dtype(self.dtype) and X.shape[1] == self.widths[0]
@@ -204,13 +233,15 @@ class Segment:
         _check(lib().slp_segment_forward(self._h, _ptr(X), X.shape[0], _ptr(out), _stream()))
         return out
 
-    def input_grad(self, X, targets):
+    def input_grad(self, X, targets, loss_out=None):
         """slp_segment_input_grad: (d loss / d X, device scalar loss); parameters untouched."""
         assert X.is_cuda and X.is_contiguous() and X.dtype == _torch_dtype(self.dtype) and X.shape[1] == self.widths[0]
         assert targets.dtype == torch.int32 and targets.numel() == X.shape[0]
+        dst = self._loss if loss_out is None else loss_out
+        assert dst.dtype == torch.float32 and dst.numel() == 1 and dst.is_cuda
         dX = torch.empty_like(X)
-        _check(lib().slp_segment_input_grad(self._h, _ptr(X), _ptr(targets), X.shape[0], _ptr(dX), _ptr(self._loss), _stream()))
-        return dX, self._loss
+        _check(lib().slp_segment_input_grad(self._h, _ptr(X), _ptr(targets), X.shape[0], _ptr(dX), _ptr(dst), _stream()))
+        return dX, dst
 
     def step_external(self, X, dA_out):
         """slp_segment_step_external: training step from a gradient w.r.t. the segment output."""

@@ -32,6 +32,7 @@ UNITS = {
     "elementwise.hip": [],
     "gemm.hip": [],
     "probe.hip": [],
+    "accuracy.hip": [],
 }
 
 

@@ -730,6 +730,26 @@ int slp_segment_step_external(slp_segment* seg, const void* X, const void* dA_ou
   return SLP_OK;
 }
 
+int slp_count_correct(const void* logits, const int32_t* targets, int batch, int classes, int dt, void* scratch,
+                      size_t scratch_bytes, int accumulate, int64_t* correct_out, slp_stream stream) {
+  if (!logits || !targets || !scratch || !correct_out) return fail(SLP_ERR_ARG, "slp_count_correct: null pointer");
+  if (batch <= 0 || classes <= 0) return fail(SLP_ERR_ARG, "slp_count_correct: batch and classes must be positive (got %d, %d)", batch, classes);
+  if (dt != SLP_F32 && dt != SLP_BF16) return fail(SLP_ERR_ARG, "slp_count_correct: unknown dtype %d", dt);
+  const size_t need = (size_t)count_partials(batch) * sizeof(int32_t);
+  if (scratch_bytes < need || ((uintptr_t)scratch & 3))
+    return fail(SLP_ERR_ALLOC, "slp_count_correct: scratch of %zu bytes (4-byte aligned) needed, %zu given", need, scratch_bytes);
+  HIP_TRY(launch_count_correct(dt, logits, targets, batch, classes, (int32_t*)scratch, accumulate, (long long*)correct_out,
+                               (hipStream_t)stream));
+  return SLP_OK;
+}
+
+int slp_mean_loss(const float* losses, int n, float* mean_out, slp_stream stream) {
+  if (!losses || !mean_out) return fail(SLP_ERR_ARG, "slp_mean_loss: null pointer");
+  if (n <= 0) return fail(SLP_ERR_ARG, "slp_mean_loss: n must be positive (got %d)", n);
+  HIP_TRY(launch_reduce_loss(losses, n, 1.0 / (double)n, mean_out, nullptr, (hipStream_t)stream));
+  return SLP_OK;
+}
+
 int slp_segment_profile_enable(slp_segment* seg, int on) {
   int rc = check_seg(seg, false, false);
   if (rc) return rc;

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 namespace slp {
 
 // Leading dimensions of every internal buffer are multiples of this many elements,
@@ -88,6 +90,13 @@ hipError_t launch_make_labels(uint64_t seed, int classes, int dim, int dist, flo
 hipError_t launch_make_inputs(uint64_t seed, const float* table, int classes, const int32_t* y, int64_t first_sample,
                               int batch, int dim, float sigma, void* out, int dt, hipStream_t s);
 hipError_t launch_init_weights(uint64_t seed, int layer, float* W32, int N, int K, int ldk, float* b, hipStream_t s);
+
+// Rows whose arg-max logit (lowest index among equal values) equals the row's class: logits[batch][classes] dense,
+// partials = count_partials(batch) int32 of scratch (one per block of four rows, each written before it is read),
+// *out = (accumulate ? *out : 0) + count.
+int count_partials(int batch);
+hipError_t launch_count_correct(int dtype, const void* logits, const int32_t* y, int batch, int classes, int32_t* partials,
+                                int accumulate, long long* out, hipStream_t s);
 
 // Sets the one-time attributes of every matrix-product kernel instantiation (needs a current device).
 hipError_t gemm_configure_all();

@@ -22,6 +22,16 @@ partition k-1 against its own label table (Sec. 2, the multi-partition variant).
 
 import torch
 
+from . import api
+
+
+def _epoch_means(losses):
+    """losses[epochs][batches] (float32, device) -> list of per-epoch means, each reduced by the library."""
+    means = torch.empty(losses.shape[0], dtype=torch.float32, device=losses.device)
+    for ep in range(losses.shape[0]):
+        api.mean_loss(losses[ep], out=means[ep:ep + 1])
+    return means.tolist()
+
 
 def _batches(n, batch):
     for s in range(0, n, batch):
@@ -43,10 +53,10 @@ def train_epochs(seg, X, y, epochs, batch, staged=False):
             if staged:
                 Xs[:b - a].copy_(X[a:b])
                 ys[:b - a].copy_(y[a:b])
-                losses[ep, i] = seg.step(Xs[:b - a], ys[:b - a])[0]
+                seg.step(Xs[:b - a], ys[:b - a], loss_out=losses[ep, i:i + 1])
             else:
-                losses[ep, i] = seg.step(X[a:b], y[a:b])[0]
-    return losses.mean(dim=1).tolist()
+                seg.step(X[a:b], y[a:b], loss_out=losses[ep, i:i + 1])
+    return _epoch_means(losses)
 
 
 def store_response(seg, X, batch):
@@ -77,10 +87,9 @@ def recovery_epochs(left, right, X, y, epochs, batch):
     for ep in range(epochs):
         for i, (a, b) in enumerate(_batches(n, batch)):
             resp = left.forward(X[a:b])
-            d_resp, loss = right.input_grad(resp, y[a:b])
-            losses[ep, i] = loss[0]
+            d_resp, _ = right.input_grad(resp, y[a:b], loss_out=losses[ep, i:i + 1])
             left.step_external(X[a:b], d_resp)
-    return losses.mean(dim=1).tolist()
+    return _epoch_means(losses)
 
 
 def train_simultaneous(segments, tables, X, y, epochs, batch, noise_seed=5, sigma=0.05):
@@ -89,7 +98,6 @@ def train_simultaneous(segments, tables, X, y, epochs, batch, noise_seed=5, sigm
     sample index, seed noise_seed + k) instead of the response of partition k-1, so no partition waits for another.
     tables[k] is the float32 label table of cut k (already bound to segments[k] as its target).  Each partition
     steps on a stream of its own.  Returns the mean loss of each epoch, per partition."""
-    from . import api
     n = X.shape[0]
     nb = (n + batch - 1) // batch
     losses = [torch.zeros((epochs, nb), dtype=torch.float32, device=X.device) for _ in segments]
@@ -102,11 +110,11 @@ def train_simultaneous(segments, tables, X, y, epochs, batch, noise_seed=5, sigm
             for k, (seg, st) in enumerate(zip(segments, streams)):
                 with torch.cuda.stream(st):
                     xin = X[a:b] if k == 0 else api.make_segment_inputs(noise_seed + k, tables[k - 1], y[a:b], a, sigma, seg.dtype)
-                    losses[k][ep, i] = seg.step(xin, y[a:b])[0]
+                    seg.step(xin, y[a:b], loss_out=losses[k][ep, i:i + 1])
                     xin.record_stream(st)
     for st in streams:
         cur.wait_stream(st)
-    return [l.mean(dim=1).tolist() for l in losses]
+    return [_epoch_means(l) for l in losses]
 
 
 def joined_forward(segments, X, batch):
@@ -118,5 +126,12 @@ def joined_forward(segments, X, batch):
 
 
 def accuracy(segments, X, y, batch):
-    logits = joined_forward(segments, X, batch)
-    return float((logits.float().argmax(dim=1) == y.long()).float().mean().item())
+    """Fraction of samples whose arg-max logit of the joined network is their class: the batches go through the chain
+    of forward passes one at a time and the library counts the hits of each into one device counter."""
+    hits = torch.zeros(1, dtype=torch.int64, device=X.device)
+    for a, b in _batches(X.shape[0], batch):
+        cur = X[a:b]
+        for seg in segments:
+            cur = seg.forward(cur)
+        api.count_correct(cur, y[a:b], out=hits, accumulate=True)
+    return int(hits.item()) / X.shape[0]

@@ -456,7 +456,7 @@ def test_recovery_steps_against_autodiff_library():
 # ---------------------------------------------------------------------------------
 # ReLU decisions at ties
 # ---------------------------------------------------------------------------------
-def test_tie_decisions_are_taken_only_inside_the_band():
+def test_tie_decisions_are_taken_only_inside_the_bounds():
     # hand-built 2-2-1 net: unit 0 of layer 1 has pre-activation exactly 0 for sample 0 (a tie), everything else is clear
     seg = osg.Segment([2, 2, 1], osg.RELU_HIDDEN_IDENTITY_LAST, osg.MSE_SIL, lr=0.1, momentum=0.0)
     seg.set_params(0, np.array([[1.0, -1.0], [0.5, 0.5]]), np.array([0.0, 0.0]))
@@ -469,17 +469,99 @@ def test_tie_decisions_are_taken_only_inside_the_band():
     # own decision at the tie: inactive (the derivative of ReLU at 0 is taken as 0)
     # out = [3, 6.5]; G = 2*(out - 0)/2 = out; dZ1 = G * W2 * mask
     assert np.array_equal(own["dZ"][1], np.array([[0.0, 9.0], [13.0, 19.5]]))
-    same = seg.step(X, y, T, update=False, tie_decisions=[None, own["A"][1] > 0, None])
-    assert same["ties_taken"] == 0 and same["decisions_refused"] == 0
+    E = seg.forward_error_bound(X)
+    # the bound by hand for (sample 0, unit 0): (sqrt(2) + 2) 2^-24 (|1*1| + |1*-1| + 0)
+    assert math.isclose(E[1][0, 0], (math.sqrt(2) + 2) * 2.0 ** -24 * 2.0, rel_tol=1e-14)
+    assert np.all(E[1] < 2e-6) and np.all(E[1] > 0)
+    same = seg.step(X, y, T, update=False, tie_decisions=[None, own["A"][1] > 0, None], tie_bounds=E)
+    assert same["ties_taken"] == 0 and same["decisions_refused"] == 0 and not same["tie_rows"].any()
     assert np.array_equal(same["dZ"][1], own["dZ"][1])
     # the other side calls the tie "active": taken over, the gradient flows through that unit
     other = np.array([[True, True], [True, True]])
-    took = seg.step(X, y, T, update=False, tie_decisions=[None, other, None])
+    took = seg.step(X, y, T, update=False, tie_decisions=[None, other, None], tie_bounds=E)
     assert took["ties_taken"] == 1 and took["decisions_refused"] == 0
+    assert np.array_equal(took["tie_rows"], [True, False]) and took["worst_tie_ratio"] == 0.0
     assert np.array_equal(took["dZ"][1], np.array([[6.0, 9.0], [13.0, 19.5]]))
     assert np.array_equal(took["dW"][0], took["dZ"][1].T @ X)
-    # a disagreement at a clear pre-activation (1.5, far outside the band) is refused and counted
+    # a disagreement at a clear pre-activation (1.5, far outside the bound) is refused and counted
     wrong = np.array([[False, True], [True, False]])
-    ref = seg.step(X, y, T, update=False, tie_decisions=[None, wrong, None])
+    ref = seg.step(X, y, T, update=False, tie_decisions=[None, wrong, None], tie_bounds=E)
     assert ref["ties_taken"] == 0 and ref["decisions_refused"] == 1
     assert np.array_equal(ref["dZ"][1], own["dZ"][1])
+    # a pre-activation of 1e-5 is NOT a tie for float32 accumulation of two terms of size 1
+    seg.set_params(0, np.array([[1.0, -1.0 + 1e-5], [0.5, 0.5]]), np.array([0.0, 0.0]))
+    E = seg.forward_error_bound(X)
+    ref = seg.step(X, y, T, update=False, tie_decisions=[None, np.array([[False, True], [True, True]]), None], tie_bounds=E)
+    assert ref["ties_taken"] == 0 and ref["decisions_refused"] == 1
+
+
+def test_stored_deviation_against_brute_force():
+    # bf16 storage: two values within E of each other round to the same bfloat16 unless a rounding boundary lies
+    # between them; the bound must hold for every sampled neighbour, and be zero only where all neighbours agree
+    seg = osg.Segment([2, 2], osg.RELU_ALL, osg.MSE_SIL, mode="bf16")
+    g = np.random.default_rng(3)
+    pre = np.concatenate([g.standard_normal(4000), g.standard_normal(2000) * 1e-3, [0.0, 1.0, 2.0, 0.5, 1.00390625, 0.998046875]])
+    for E in (1e-7, 3e-5, 2e-3):
+        bound = seg._stored_deviation(pre, np.full(pre.shape, E))
+        worst = np.zeros_like(pre)
+        for t in np.linspace(-1.0, 1.0, 41):
+            other = torch.tensor((pre + t * E).astype(np.float32)).to(torch.bfloat16).double().numpy()
+            mine = torch.tensor(pre.astype(np.float32)).to(torch.bfloat16).double().numpy()
+            worst = np.maximum(worst, np.abs(other - mine))
+        assert np.all(worst <= bound * (1 + 1e-12) + 1e-300)
+        assert np.all(worst[bound == 0.0] == 0.0)
+        # not vacuous: for a small E most values are far from a boundary and get a zero bound
+        if E == 1e-7:
+            assert np.mean(bound == 0.0) > 0.95 and np.any(bound > 0.0)
+    # fp32 mode stores the value itself
+    seg32 = osg.Segment([2, 2], osg.RELU_ALL, osg.MSE_SIL)
+    assert np.array_equal(seg32._stored_deviation(pre, np.full(pre.shape, 1e-5)), np.full(pre.shape, 1e-5))
+
+
+@pytest.mark.parametrize("mode", ["fp32", "bf16"])
+def test_forward_error_bound_covers_a_float32_implementation(mode):
+    # another implementation of the forward pass: float32 accumulation (torch CPU, any order), same storage points.
+    # Its pre-activations must lie within the oracle's bounds of the oracle's own, layer after layer, and the bounds
+    # must stay small against the pre-activations (they decide where a ReLU decision counts as a tie)
+    widths = [784, 1024, 512, 256]
+    seg = _rand_segment(widths, osg.RELU_ALL, osg.MSE_SIL, 4, mode=mode)
+    X, _ = datagen.class_mean_inputs(96, 47, dim=784, seed=2)
+    store = (lambda t: t.to(torch.bfloat16).to(torch.float32)) if mode == "bf16" else (lambda t: t)
+    a = store(torch.tensor(X))
+    Xv = a.double().numpy()
+    A, Z = seg.forward_all(Xv)
+    E = seg.forward_error_bound(Xv)
+    for l in range(1, 4):
+        W = store(torch.tensor(seg.W[l - 1], dtype=torch.float32))
+        z = a @ W.T + torch.tensor(seg.b[l - 1], dtype=torch.float32)
+        dev = np.abs(z.double().numpy() - Z[l])
+        assert np.all(dev <= E[l]), (l, float(np.max(dev / E[l])))
+        band = np.max(E[l]) / np.max(np.abs(Z[l]))
+        assert band <= ((1.5e-5 if l == 1 else 5e-4) if mode == "fp32" else (1.5e-5 if l == 1 else 1.5e-2)), (l, band)
+        a = store(torch.relu(z))
+    # parameters that differ by a relative 1e-6 of the largest weight: still inside, with param_rel saying so
+    g = np.random.default_rng(1)
+    E2 = seg.forward_error_bound(Xv, param_rel=1e-6)
+    a = store(torch.tensor(X))
+    for l in range(1, 4):
+        Wm = seg.W[l - 1] + 1e-6 * np.max(np.abs(seg.W[l - 1])) * g.uniform(-1, 1, seg.W[l - 1].shape)
+        bm = seg.b[l - 1] + 1e-6 * np.max(np.abs(seg.b[l - 1])) * g.uniform(-1, 1, seg.b[l - 1].shape)
+        z = a @ store(torch.tensor(Wm, dtype=torch.float32)).T + torch.tensor(bm, dtype=torch.float32)
+        dev = np.abs(z.double().numpy() - Z[l])
+        assert np.all(dev <= E2[l]) and np.all(E2[l] >= E[l]), l
+        a = store(torch.relu(z))
+
+
+def test_sampled_weight_gradient_entries_are_entries_of_the_step_gradient():
+    seg = _rand_segment([7, 9, 5], osg.RELU_ALL, osg.MSE_SIL, 8)
+    g = np.random.default_rng(2)
+    X = g.standard_normal((11, 7))
+    T = g.standard_normal((3, 5))
+    out = seg.step(X, np.arange(11) % 3, T, update=False)
+    oi, ki = np.array([0, 8, 3, 3]), np.array([6, 0, 2, 5])
+    got, scale = osg.weight_gradient_elements(out["dZ"][1][:, oi], out["A"][0][:, ki])
+    assert np.allclose(got, out["dW"][0][oi, ki], rtol=1e-13, atol=1e-16)
+    assert np.all(scale >= np.abs(got))
+    # second layer, through python loops
+    got2, _ = osg.weight_gradient_elements(out["dZ"][2][:, [4]], out["A"][1][:, [7]])
+    assert math.isclose(got2[0], sum(out["dZ"][2][n, 4] * out["A"][1][n, 7] for n in range(11)), rel_tol=1e-13)
