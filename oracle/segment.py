@@ -78,6 +78,20 @@ def gemm_flops_per_sample(widths):
     return 6 * P - 2 * widths[0] * widths[1]
 
 
+def count_correct(logits, y):
+    """Rows whose largest logit sits at the row's class (paper Sec. 4 reports the joined
+    network's accuracy on the test set: this count over the number of rows).  Among equal
+    maxima the lowest index is the prediction."""
+    logits = np.asarray(logits)
+    y = np.asarray(y, dtype=np.int64)
+    return int(np.sum(np.argmax(logits, axis=1) == y))
+
+
+def mean_loss(losses):
+    """Epoch figure of a training curve: the mean of its per-step losses."""
+    return float(np.mean(np.asarray(losses, dtype=np.float64)))
+
+
 def weight_gradient_elements(dZ_cols, A_cols):
     """Sampled entries of a weight gradient from their definition: entry s is
     dW[o_s, k_s] = sum_n dZ[n, o_s] A[n, k_s], with dZ_cols[:, s] = dZ[:, o_s] and

@@ -191,3 +191,34 @@ def test_simultaneous_training_of_three_partitions_against_the_oracle():
         assert got[k][1] < got[k][0]                                   # every partition learns
         for l in range(2):
             assert rel_err(to_np(gs[k].get_params(l)[0]), os_[k].W[l]) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+@pytest.mark.parametrize("batch,classes", [(1, 1), (3, 47), (257, 100), (4096, 1000), (1410, 47)])
+def test_count_correct_is_exact(dtype, batch, classes):
+    # seeded logits on a coarse grid, so that equal maxima occur; the same values go to both sides and the count is an
+    # integer: it must be equal, ties and ragged batches included, and accumulate over calls
+    g = np.random.default_rng(batch * 7 + classes)
+    Z = (g.integers(-8, 9, size=(batch, classes)) / 4.0).astype(np.float32)
+    y = g.integers(0, classes, batch).astype(np.int32)
+    y[: batch // 3] = np.argmax(Z[: batch // 3], axis=1)            # a good share of hits
+    if batch > 2:
+        y[-1] = classes + 3                                           # out of range: never a hit
+    Zd = dev(Z, dtype)
+    ref = osg.count_correct(to_np(Zd), y)
+    got = api.count_correct(Zd, torch.from_numpy(y).to(DEV))
+    assert int(got.item()) == ref
+    api.count_correct(Zd, torch.from_numpy(y).to(DEV), out=got, accumulate=True)
+    assert int(got.item()) == 2 * ref
+    with pytest.raises(api.SlpError) as e:
+        api._check(api.lib().slp_count_correct(api._ptr(Zd), api._ptr(torch.from_numpy(y).to(DEV)), batch, classes, dtype,
+                                               api._ptr(got), 0, 0, api._ptr(got), None))
+    assert e.value.code == -3                                         # scratch too small
+
+
+def test_mean_loss_matches_the_definition():
+    g = np.random.default_rng(3)
+    for n in (1, 7, 441, 5000):
+        x = g.uniform(0.1, 3.0, n).astype(np.float32)
+        got = float(api.mean_loss(torch.from_numpy(x).to(DEV)).item())
+        assert abs(got - osg.mean_loss(x)) <= 1e-6 * osg.mean_loss(x)

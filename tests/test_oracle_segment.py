@@ -565,3 +565,22 @@ def test_sampled_weight_gradient_entries_are_entries_of_the_step_gradient():
     # second layer, through python loops
     got2, _ = osg.weight_gradient_elements(out["dZ"][2][:, [4]], out["A"][1][:, [7]])
     assert math.isclose(got2[0], sum(out["dZ"][2][n, 4] * out["A"][1][n, 7] for n in range(11)), rel_tol=1e-13)
+
+
+def test_count_correct_against_loops_and_ties():
+    g = np.random.default_rng(5)
+    Z = g.standard_normal((50, 7))
+    y = g.integers(0, 7, 50)
+    hits = 0
+    for n in range(50):
+        best = 0
+        for c in range(1, 7):
+            if Z[n, c] > Z[n, best]:
+                best = c
+        hits += int(best == y[n])
+    assert osg.count_correct(Z, y) == hits and 0 < hits < 50
+    # equal maxima: the lowest index is the prediction; a class id outside the row never matches
+    Z = np.array([[1.0, 3.0, 3.0], [2.0, 2.0, 2.0], [0.0, -1.0, 5.0]])
+    assert osg.count_correct(Z, [1, 0, 2]) == 3
+    assert osg.count_correct(Z, [2, 1, 7]) == 0
+    assert osg.mean_loss([1.0, 2.0, 6.0]) == 3.0
