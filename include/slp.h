@@ -238,6 +238,18 @@ int slp_count_correct(const void* logits /*device*/, const int32_t* targets /*de
                       slp_stream stream);
 int slp_mean_loss(const float* losses /*device*/, int n, float* mean_out /*device*/, slp_stream stream);
 
+/* slp_count_correct for callers that cannot allocate or hand over scratch memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same result as slp_count_correct, bit for bit; the per-block
+ * partial counts live in a 64 KiB array inside the library's code object (one copy per GPU the library runs on, held
+ * until the process ends) instead of caller memory, and the call allocates nothing and frees nothing.
+ * Limit: batch <= SLP_COUNT_STATIC_MAX_BATCH (65536 rows), else SLP_ERR_SHAPE.  Every call on a GPU uses that GPU's one
+ * array (each call overwrites the entries it reads; nothing has to be cleared): calls that overlap in time on the
+ * same GPU -- different streams, or different host threads -- race and must be serialised by the caller; calls that
+ * follow each other on one stream are safe.  Other errors as for slp_count_correct. */
+#define SLP_COUNT_STATIC_MAX_BATCH 65536
+int slp_count_correct_static(const void* logits /*device*/, const int32_t* targets /*device*/, int batch, int classes,
+                             int dt, int accumulate, int64_t* correct_out /*device*/, slp_stream stream);
+
 /* ---- measurement hooks -------------------------------------------------------------
  * When enabled, every matrix-product launch of the segment is bracketed by HIP
  * events on its stream.  slp_segment_profile_read synchronises the recorded events,

@@ -70,6 +70,7 @@ def lib():
         "slp_probe_mfma_rate": (i32, [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]),
         "slp_count_correct": (i32, [vp, vp, i32, i32, i32, vp, sz, i32, vp, vp]),
         "slp_mean_loss": (i32, [vp, i32, vp, vp]),
+        "slp_count_correct_static": (i32, [vp, vp, i32, i32, i32, i32, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -84,7 +85,8 @@ EXPORTS = ["slp_last_error", "slp_make_synthetic_labels", "slp_make_segment_inpu
            "slp_segment_get_momentum", "slp_segment_get_activation", "slp_segment_set_lr", "slp_segment_set_labels",
            "slp_segment_step", "slp_segment_forward", "slp_segment_input_grad", "slp_segment_step_external",
            "slp_segment_profile_enable", "slp_segment_profile_read", "slp_probe_mfma_rate",
-           "slp_segment_set_graph", "slp_segment_set_overlap", "slp_segment_join", "slp_count_correct", "slp_mean_loss"]
+           "slp_segment_set_graph", "slp_segment_set_overlap", "slp_segment_join", "slp_count_correct", "slp_mean_loss",
+           "slp_count_correct_static"]
 
 
 def _check(code):
@@ -140,6 +142,18 @@ def count_correct(logits, targets, out=None, accumulate=False):
     _check(lib().slp_count_correct(_ptr(logits), _ptr(targets), logits.shape[0], logits.shape[1],
                                    BF16 if logits.dtype == torch.bfloat16 else F32, _ptr(scratch), scratch.numel() * 4,
                                    int(bool(accumulate)), _ptr(out), _stream()))
+    return out
+
+
+def count_correct_static(logits, targets, out, accumulate=False):
+    """slp_count_correct_static: the same count with the partial counts in the library's static device array; `out`
+    (one int64 on the device) is the caller's, nothing is allocated here or in the library."""
+    assert logits.is_cuda and logits.is_contiguous() and logits.dim() == 2 and logits.dtype in (torch.float32, torch.bfloat16)
+    assert targets.dtype == torch.int32 and targets.numel() == logits.shape[0]
+    assert out.is_cuda and out.dtype == torch.int64 and out.numel() == 1
+    _check(lib().slp_count_correct_static(_ptr(logits), _ptr(targets), logits.shape[0], logits.shape[1],
+                                          BF16 if logits.dtype == torch.bfloat16 else F32, int(bool(accumulate)), _ptr(out),
+                                          _stream()))
     return out
 
 

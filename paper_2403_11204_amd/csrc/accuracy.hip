@@ -12,6 +12,12 @@ namespace {
 
 typedef __bf16 bf16;
 
+// Per-block partial counts of the allocation-free entry point.  Device memory that lives in
+// the code object: every GPU the library runs on holds its own copy until the process ends.
+// Host code must never pass this name to a kernel (on the host it is only a stand-in for the
+// symbol); it asks the runtime for the device address once per device and uses that.
+__device__ __align__(256) int32_t scratch[kCountStaticPartials];
+
 // One wavefront per row: arg-max with the lowest index winning among equal values (the
 // convention of the usual library arg-max), compared with the row's class; the block's four
 // rows are added and written as one partial count.
@@ -56,6 +62,10 @@ __global__ __launch_bounds__(256) void sum_counts_kernel(const int32_t* __restri
   if (threadIdx.x == 0) out[0] = (accumulate ? out[0] : 0) + red[0];
 }
 
+constexpr int kMaxDevices = 64;
+int32_t* g_static_ptr[kMaxDevices];      // device address of `scratch` on each device, filled on first use
+std::mutex g_static_mu;
+
 }  // namespace
 
 int count_partials(int batch) { return (batch + 3) / 4; }
@@ -69,6 +79,25 @@ hipError_t launch_count_correct(int dtype, const void* logits, const int32_t* y,
   if (e != hipSuccess) return e;
   sum_counts_kernel<<<1, 256, 0, s>>>(partials, blocks, accumulate, out);
   return hipGetLastError();
+}
+
+// Device address of the static partial-count array on the current device.  The symbol is looked up once per
+// device (each GPU holds its own copy at its own address); no memory is allocated.
+hipError_t count_static_scratch(int32_t** ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    int32_t* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = p;
+  }
+  *ptr = g_static_ptr[dev];
+  return hipSuccess;
 }
 
 }  // namespace slp

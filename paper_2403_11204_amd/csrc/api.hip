@@ -743,6 +743,23 @@ int slp_count_correct(const void* logits, const int32_t* targets, int batch, int
   return SLP_OK;
 }
 
+int slp_count_correct_static(const void* logits, const int32_t* targets, int batch, int classes, int dt, int accumulate,
+                             int64_t* correct_out, slp_stream stream) {
+  if (!logits || !targets || !correct_out) return fail(SLP_ERR_ARG, "slp_count_correct_static: null pointer");
+  if (batch <= 0 || classes <= 0)
+    return fail(SLP_ERR_ARG, "slp_count_correct_static: batch and classes must be positive (got %d, %d)", batch, classes);
+  if (dt != SLP_F32 && dt != SLP_BF16) return fail(SLP_ERR_ARG, "slp_count_correct_static: unknown dtype %d", dt);
+  static_assert(SLP_COUNT_STATIC_MAX_BATCH == 4 * kCountStaticPartials, "header limit and array size must agree");
+  if (batch > SLP_COUNT_STATIC_MAX_BATCH)
+    return fail(SLP_ERR_SHAPE, "slp_count_correct_static: batch %d exceeds the static scratch's limit of %d rows", batch,
+                SLP_COUNT_STATIC_MAX_BATCH);
+  int32_t* partials = nullptr;
+  HIP_TRY(count_static_scratch(&partials));      // looked up once per device; never the array's name itself
+  HIP_TRY(launch_count_correct(dt, logits, targets, batch, classes, partials, accumulate, (long long*)correct_out,
+                               (hipStream_t)stream));
+  return SLP_OK;
+}
+
 int slp_mean_loss(const float* losses, int n, float* mean_out, slp_stream stream) {
   if (!losses || !mean_out) return fail(SLP_ERR_ARG, "slp_mean_loss: null pointer");
   if (n <= 0) return fail(SLP_ERR_ARG, "slp_mean_loss: n must be positive (got %d)", n);

@@ -98,6 +98,11 @@ int count_partials(int batch);
 hipError_t launch_count_correct(int dtype, const void* logits, const int32_t* y, int batch, int classes, int32_t* partials,
                                 int accumulate, long long* out, hipStream_t s);
 
+// Partial counts held in a static device array instead of caller memory: enough for batches up to
+// 4 * kCountStaticPartials rows.  count_static_scratch returns the array's device address on the current device.
+constexpr int kCountStaticPartials = 16384;
+hipError_t count_static_scratch(int32_t** ptr);
+
 // Sets the one-time attributes of every matrix-product kernel instantiation (needs a current device).
 hipError_t gemm_configure_all();
 
