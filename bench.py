@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the segment training step on one MI355X.
 
-    python bench.py [--config 4] [--steps K] [--warmup W] [--no-cpu] [--no-e2e]
+    python bench.py [--config 4] [--steps K] [--warmup W] [--no-cpu] [--no-e2e] [--no-others]
 
 A "step" is one pass of the whole hot path -- forward, loss, backward confined to
 the segment, SGD update -- of EVERY segment of the chosen configuration over one
@@ -32,6 +32,7 @@ sys.path.insert(0, ROOT)
 from paper_2403_11204_amd import api, datagen  # noqa: E402
 
 PEAK_TFLOPS = {api.BF16: 2516.6, api.F32: 157.3}     # dense MFMA peaks of MI355X
+HBM_BYTES_PER_S = 8.0e12                             # published HBM3E rate of MI355X
 # Bytes crossing the L2 boundary per matrix-product launch (read + written), average over the 16 launches of
 # one step of the default workload: rocprofv3 FETCH_SIZE / WRITE_SIZE passes scaled by a 1 GiB copy kernel in
 # the same process (profiles/comparison_config_gemm_hbm_traffic.md).  Valid for the kernel those passes ran;
@@ -71,8 +72,8 @@ def gemm_flops_per_sample(widths):
     return 6 * P - 2 * widths[0] * widths[1]
 
 
-def build_segments(cfg, n_batches):
-    """Handles, label tables and per-segment inputs for n_batches resident batches."""
+def build_segments(cfg, n_batches, only=None):
+    """Handles, label tables and per-segment inputs for n_batches resident batches (only: that segment alone)."""
     dt, B, classes = cfg["dtype"], cfg["batch"], cfg["classes"]
     tdt = torch.bfloat16 if dt == api.BF16 else torch.float32
     ys, X0 = [], []
@@ -83,6 +84,13 @@ def build_segments(cfg, n_batches):
     segs, inputs = [], []
     prev_table = None
     for si, (widths, act, loss, dist, seed) in enumerate(cfg["segs"]):
+        table = None
+        if loss == MSE and (only is None or si == only or si + 1 == only):
+            table = api.make_synthetic_labels(seed, classes, widths[-1], dist, cfg.get("kappa", 1.0), api.F32)
+        if only is not None and si != only:
+            if si + 1 == only:          # the one table the wanted segment's inputs are made from
+                prev_table = table
+            continue
         seg = api.Segment(widths, act, loss, max_batch=B, dtype=dt, lr=cfg["lr"], momentum=cfg["mom"])
         seg.init(100 + si)
         if cfg.get("graph"):        # launch-bound sizes: replay the captured launch sequence of a step
@@ -94,9 +102,13 @@ def build_segments(cfg, n_batches):
         else:   # an interior/final segment sees the previous cut's label of the class plus noise (sigma 0.05)
             inputs.append([api.make_segment_inputs(5 + si, prev_table, ys[i], i * B, 0.05, dt) for i in range(n_batches)])
         if loss == MSE:
-            prev_table = api.make_synthetic_labels(seed, classes, widths[-1], dist, cfg.get("kappa", 1.0), api.F32)
-            seg.set_labels(prev_table)
+            prev_table = table
+            seg.set_labels(table)
         segs.append(seg)
+    if only is not None:
+        prev_table = None
+        if only != 0:
+            del X0
     return segs, inputs, ys
 
 
@@ -143,8 +155,13 @@ def time_workload(segs, inputs, ys, use_streams, steps, warmup, profile=True):
     return wall_ms / steps, ev0.elapsed_time(ev1) / steps, prof
 
 
-def cpu_baseline(cfg, rows, max_seconds=60.0):
-    """The CPU oracle, as it stands, on `rows` rows of the same workload (all segments)."""
+def cpu_baseline(cfg, rows):
+    """The CPU oracle, as it stands, on a reduced batch of the same workload (all segments, full widths).
+
+    A step of the oracle costs a part that does not depend on the batch (rounding every weight to bf16, the float64
+    update of every parameter) plus a part per row (the matrix products).  Two steps are timed, on rows/4 and on rows
+    rows, and the two parts separated from them, so that the reader can scale: `value` is what was measured at `rows`
+    rows; `at_full_batch` extrapolates the same two costs to the configuration's batch."""
     from oracle import rng as orng
     from oracle import segment as osg
     try:
@@ -154,12 +171,12 @@ def cpu_baseline(cfg, rows, max_seconds=60.0):
         cores = os.cpu_count()
     mode = "bf16" if cfg["dtype"] == api.BF16 else "fp32"
     classes = cfg["classes"]
+    small = max(1, rows // 4)
     X, y = datagen.class_mean_inputs(rows, classes, dim=784, seed=1)
-    total, prev = 0.0, None
+    t_small, t_rows, prev = 0.0, 0.0, None
     for si, (widths, act, loss, dist, seed) in enumerate(cfg["segs"]):
         o = osg.Segment(widths, act, loss, lr=cfg["lr"], momentum=cfg["mom"], mode=mode)
-        for l in range(o.L):
-            W, b = orng.init_weights(100 + si, l, widths[l + 1], widths[l])
+        for l, (W, b) in enumerate(datagen.uniform_weights(widths, 100 + si)):
             o.set_params(l, W, b)
         xin = X if si == 0 else orng.make_segment_inputs(5 + si, prev, y, 0, 0.05)
         table = None
@@ -167,11 +184,77 @@ def cpu_baseline(cfg, rows, max_seconds=60.0):
             table = orng.make_synthetic_labels(seed, classes, widths[-1], dist, cfg.get("kappa", 1.0))
             prev = table
         t0 = time.perf_counter()
+        o.step(xin[:small], y[:small], table)
+        t1 = time.perf_counter()
         o.step(xin, y, table)
-        total += time.perf_counter() - t0
+        t2 = time.perf_counter()
+        t_small += t1 - t0
+        t_rows += t2 - t1
         del o
-    return {"value": rows / total, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
-            "sample": "one step of every segment at full widths on %d rows (%.1f s of CPU time)" % (rows, total)}
+    per_row = max(t_rows - t_small, 0.0) / max(rows - small, 1)
+    fixed = max(t_rows - per_row * rows, 0.0)
+    B = cfg["batch"]
+    return {"value": rows / t_rows, "unit": "samples/s", "cores": int(cores), "kind": "oracle", "rows": rows,
+            "seconds": t_rows, "fixed_seconds_per_step": fixed, "seconds_per_row": per_row,
+            "product_share_of_step": per_row * rows / t_rows if t_rows > 0 else None,
+            "at_full_batch": {"batch": B, "samples_per_s": B / (fixed + per_row * B), "kind": "extrapolated from the two costs"},
+            "sample": "one step of every segment at full widths on %d rows (%.1f s of CPU time; a %d-row step before it, "
+                      "%.1f s, separates the batch-independent cost from the per-row cost); the oracle's matrix products "
+                      "are numpy float64 products, i.e. the host's BLAS on %d threads" % (rows, t_rows, small, t_small, int(cores))}
+
+
+def measure_segment_peaks(cfg, steps=3):
+    """Peak device memory of segment-wise training, measured: every segment is built, stepped a few times and freed
+    on its own, which is how the method trains (only one partition's parameters, optimiser state and activations
+    are resident at a time)."""
+    peaks = []
+    for si in range(len(cfg["segs"])):
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats()
+        base = torch.cuda.memory_allocated()
+        sub = dict(cfg)
+        segs, inputs, ys = build_segments(sub, n_batches=1, only=si)
+        for _ in range(steps):
+            segs[0].step(inputs[0][0], ys[0], want_loss=True)
+        segs[0].join()
+        torch.cuda.synchronize()
+        peaks.append(int(torch.cuda.max_memory_allocated() - base))
+        del segs, inputs, ys
+    torch.cuda.empty_cache()
+    return peaks
+
+
+def quick_config(cid, steps, warmup):
+    """ms per step, TFLOP/s and fractions of another configuration, measured the same way as the main workload."""
+    cfg = dict(CONFIGS[cid])
+    cfg["overlap"] = False
+    segs, inputs, ys = build_segments(cfg, n_batches=2)
+    torch.cuda.synchronize()
+    if cfg.get("graph"):
+        with torch.cuda.stream(torch.cuda.Stream()):
+            wall_ms, ev_ms, _ = time_workload(segs, inputs, ys, False, steps, warmup, profile=False)
+            _, _, prof = time_workload(segs, inputs, ys, False, max(steps // 4, 10), 2)
+    else:
+        wall_ms, ev_ms, prof = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup)
+    ms = max(wall_ms, ev_ms) if not cfg["streams"] else wall_ms
+    B, peak = cfg["batch"], PEAK_TFLOPS[cfg["dtype"]]
+    flops_step = sum(gemm_flops_per_sample(s[0]) for s in cfg["segs"]) * B
+    gemm_ms, gemm_fl = sum(p[0] for p in prof), sum(p[2] for p in prof)
+    n_params = sum(sum((w[i] + 1) * w[i + 1] for i in range(len(w) - 1)) for w in (s[0] for s in cfg["segs"]))
+    out = {"workload": cfg["name"], "global_batch": B, "steps": steps, "ms_per_step": ms, "samples_per_s": B / (ms * 1e-3),
+           "step_tflops": flops_step / (ms * 1e-3) / 1e12, "step_frac_of_mfma_peak": flops_step / (ms * 1e-3) / 1e12 / peak,
+           # launch-by-launch events overlap when the segments run concurrently: no per-kernel rate then
+           "gemm_tflops": gemm_fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 and not cfg["streams"] else None,
+           "launch": "hip graph replay" if cfg.get("graph") else "eager",
+           "concurrent_streams": len(segs) if cfg["streams"] else 1,
+           # the other roof: every parameter streams through the step once per product that reads it and through the
+           # update (24 B with momentum in bf16 mode: g, v, w read; v, w, bf16 copy, transposed copy written)
+           "param_bytes_per_step_algorithmic": 24 * n_params if cfg["dtype"] == api.BF16 else 28 * n_params,
+           "hbm_floor_ms": (24 if cfg["dtype"] == api.BF16 else 28) * n_params / HBM_BYTES_PER_S * 1e3}
+    del segs, inputs, ys
+    torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -182,6 +265,7 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=sorted(CONFIGS))
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-e2e", action="store_true", help="skip the end-to-end backprop comparison (config 4)")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the wide and deep configurations (config 4)")
     ap.add_argument("--cpu-rows", type=int, default=None)
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run one plain 1 GiB -> 1 GiB elementwise copy kernel (scale reference for HBM byte counters)")
@@ -259,10 +343,10 @@ def main():
     out["roofline"]["sustained_mfma_only"] = sustained
     out["roofline"]["frac_of_sustained"] = achieved / sustained
 
+    segs = inputs = None          # everything below runs with the main workload's segments freed
+    torch.cuda.empty_cache()
     if args.config == 4 and not args.no_e2e:
         # conventional end-to-end backprop through all six layers on the same GPU, same library
-        del segs, inputs
-        torch.cuda.empty_cache()
         torch.cuda.reset_peak_memory_stats()
         e2e = api.Segment(E2E_WIDTHS, LAST, CE, max_batch=B, dtype=dt, lr=cfg["lr"], momentum=cfg["mom"])
         e2e.init(200)
@@ -278,13 +362,24 @@ def main():
             "widths": E2E_WIDTHS, "ms_per_step": m, "samples_per_s": B / (m * 1e-3), "tflops": fl / (m * 1e-3) / 1e12,
             "params_bytes": e2e.param_bytes, "workspace_bytes": e2e.workspace_bytes,
             "peak_hbm_bytes_torch": int(torch.cuda.max_memory_allocated()),
-            "segmentwise_peak_bytes": max(p_ + w_ for p_, w_ in seg_bytes),
             "segmentwise_ms_per_step": ms}
-        del e2e
+        del e2e, X0
         torch.cuda.empty_cache()
+        # the method's memory claim (Sec. 2.1), measured: each segment built, trained and freed on its own
+        peaks = measure_segment_peaks(cfg)
+        out["end_to_end_baseline"]["segmentwise_peak_bytes_measured"] = max(peaks)
+        out["end_to_end_baseline"]["segmentwise_peak_bytes_per_segment"] = peaks
+        out["end_to_end_baseline"]["segmentwise_peak_bytes_arithmetic"] = max(p_ + w_ for p_, w_ in seg_bytes)
+        out["end_to_end_baseline"]["both_segments_resident_peak_bytes"] = out["peak_hbm_bytes_torch"]
+
+    if args.config == 4 and not args.no_others:
+        # the other large-width configurations, short runs (their own lines: --config 2 / --config 3)
+        ys = None
+        torch.cuda.empty_cache()
+        out["other_configs"] = [quick_config(2, 200, 20), quick_config(3, 10, 3)]
 
     if not args.no_cpu:
-        rows = args.cpu_rows or {0: 64, 1: 256, 2: 256, 3: 16, 4: 8, 5: 1410}[args.config]
+        rows = args.cpu_rows or {0: 64, 1: 256, 2: 256, 3: 256, 4: 256, 5: 1410}[args.config]
         out["cpu_baseline"] = cpu_baseline(cfg, rows)
     print(json.dumps(out), flush=True)
 
