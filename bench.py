@@ -95,6 +95,8 @@ def build_segments(cfg, n_batches, only=None):
         seg.init(100 + si)
         if cfg.get("graph"):        # launch-bound sizes: replay the captured launch sequence of a step
             seg.set_graph(True)
+        if cfg.get("fused"):        # optimiser step inside the weight-gradient products (pays on short products)
+            seg.set_fused_update(cfg["fused"])
         if cfg.get("overlap"):      # segments stepped one after another: the update tail of one runs beside the next
             seg.set_overlap(True)
         if si == 0:
@@ -229,6 +231,8 @@ def quick_config(cid, steps, warmup):
     """ms per step, TFLOP/s and fractions of another configuration, measured the same way as the main workload."""
     cfg = dict(CONFIGS[cid])
     cfg["overlap"] = False
+    if cfg.get("graph"):
+        cfg["fused"] = 2
     segs, inputs, ys = build_segments(cfg, n_batches=2)
     torch.cuda.synchronize()
     if cfg.get("graph"):
@@ -246,7 +250,7 @@ def quick_config(cid, steps, warmup):
            "step_tflops": flops_step / (ms * 1e-3) / 1e12, "step_frac_of_mfma_peak": flops_step / (ms * 1e-3) / 1e12 / peak,
            # launch-by-launch events overlap when the segments run concurrently: no per-kernel rate then
            "gemm_tflops": gemm_fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 and not cfg["streams"] else None,
-           "launch": "hip graph replay" if cfg.get("graph") else "eager",
+           "launch": "hip graph replay" if cfg.get("graph") else "eager", "fused_update": cfg.get("fused", 0),
            "concurrent_streams": len(segs) if cfg["streams"] else 1,
            # the other roof: every parameter streams through the step once per product that reads it and through the
            # update (24 B with momentum in bf16 mode: g, v, w read; v, w, bf16 copy, transposed copy written)
@@ -270,6 +274,8 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run one plain 1 GiB -> 1 GiB elementwise copy kernel (scale reference for HBM byte counters)")
     ap.add_argument("--eager", action="store_true", help="configs 0-2: launch every kernel of a step instead of replaying graphs")
+    ap.add_argument("--fused", type=int, nargs="?", const=1, default=0, help="apply the update in the epilogue of the weight-gradient products")
+    ap.add_argument("--unfused", action="store_true", help="configs 0-2 and 5: separate update launches instead of the fused update")
     ap.add_argument("--serial", action="store_true", help="config 3: run the four segments one after another on one stream")
     ap.add_argument("--no-overlap", action="store_true",
                     help="end every step by waiting for its parameter updates (slp_segment_set_overlap off)")
@@ -280,6 +286,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     cfg = dict(CONFIGS[args.config])
+    if cfg.get("graph"):         # small and mid-size layers: the update inside the weight-gradient products (rule 2)
+        cfg["fused"] = 2
+    if args.fused:
+        cfg["fused"] = args.fused
+    if args.unfused:
+        cfg["fused"] = False
     if args.serial:
         cfg["streams"] = False
     if args.concurrent:
@@ -327,7 +339,7 @@ def main():
                    "segments": [s[0] for s in cfg["segs"]], "optimizer": "sgd lr %g momentum %g" % (cfg["lr"], cfg["mom"]),
                    "concurrent_streams": len(segs) if cfg["streams"] else 1,
                    "launch": "hip graph replay" if cfg.get("graph") and not args.eager else "eager",
-                   "update_overlap": bool(cfg["overlap"])},
+                   "update_overlap": bool(cfg["overlap"]), "fused_update": cfg.get("fused", 0)},
         "step_tflops": flops_step / (ms * 1e-3) / 1e12,
         "step_frac_of_mfma_peak": flops_step / (ms * 1e-3) / 1e12 / peak,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,

@@ -205,6 +205,19 @@ int slp_segment_step_external(slp_segment* seg, const void* X /*device*/, const 
  * and step on that to have a single combination).  Off by default. */
 int slp_segment_set_graph(slp_segment* seg, int on);
 
+/* ---- optimiser step inside the weight-gradient product (Sec. 3: SGD with momentum) ----------------------
+ * With the fused update on, the matrix product that forms dW_l applies v = mu v + dW; w = w - lr v to the tile of the
+ * weight matrix it holds and rewrites the bf16 and transposed copies from there: the gradient is never written to
+ * memory and never read back (20 instead of 28 bytes per parameter and step in bf16 mode), and a step of a small
+ * segment ends with its last product instead of a tail of update launches (the paper's own network, Sec. 3: 0.20 ->
+ * 0.14 ms per step of both partitions).  It pays where a layer's products are short; for very wide layers the separate
+ * update, which streams beside the next products, is faster.  on = 0: off (default); 1: every layer; 2: the layers
+ * where it measured faster, those with at most 4,194,304 weights; on > 2: the layers with at most `on` weights.
+ * Results equal the separate update's to float32 rounding (the same expressions on the same values).  For a layer
+ * that is fused, slp_segment_get_grads returns the bias gradient only (a request for dW fails with SLP_ERR_STATE).
+ * Drops captured graphs.  Errors: SLP_ERR_ARG (null handle, on < 0). */
+int slp_segment_set_fused_update(slp_segment* seg, int on);
+
 /* ---- several segments trained side by side (end of Sec. 2: partitions are independent jobs) ----
  * The last thing a step does is stream every parameter once (the SGD update); it runs on a stream of the handle
  * beside the matrix products that are still to come, and the step normally ends by making `stream` wait for it.

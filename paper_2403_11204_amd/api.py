@@ -65,6 +65,7 @@ def lib():
         "slp_segment_profile_enable": (i32, [vp, i32]),
         "slp_segment_set_graph": (i32, [vp, i32]),
         "slp_segment_set_overlap": (i32, [vp, i32]),
+        "slp_segment_set_fused_update": (i32, [vp, i32]),
         "slp_segment_join": (i32, [vp, vp]),
         "slp_segment_profile_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]),
         "slp_probe_mfma_rate": (i32, [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]),
@@ -86,7 +87,7 @@ EXPORTS = ["slp_last_error", "slp_make_synthetic_labels", "slp_make_segment_inpu
            "slp_segment_step", "slp_segment_forward", "slp_segment_input_grad", "slp_segment_step_external",
            "slp_segment_profile_enable", "slp_segment_profile_read", "slp_probe_mfma_rate",
            "slp_segment_set_graph", "slp_segment_set_overlap", "slp_segment_join", "slp_count_correct", "slp_mean_loss",
-           "slp_count_correct_static"]
+           "slp_count_correct_static", "slp_segment_set_fused_update"]
 
 
 def _check(code):
@@ -221,6 +222,12 @@ class Segment:
     def get_grads(self, layer):
         return self._get(lib().slp_segment_get_grads, layer)
 
+    def get_bias_grad(self, layer):
+        """slp_segment_get_grads for the bias alone (the only stored gradient while the fused update is on)."""
+        b = torch.empty((self.widths[layer + 1],), dtype=torch.float32, device=self.device)
+        _check(lib().slp_segment_get_grads(self._h, layer, None, _ptr(b), 1, _stream()))
+        return b
+
     def get_momentum(self, layer):
         return self._get(lib().slp_segment_get_momentum, layer)
 
@@ -273,6 +280,10 @@ class Segment:
     def set_overlap(self, on=True):
         """slp_segment_set_overlap: step() returns with the parameter updates still running beside the caller's next work."""
         _check(lib().slp_segment_set_overlap(self._h, int(bool(on))))
+
+    def set_fused_update(self, on=True):
+        """slp_segment_set_fused_update: the weight-gradient products apply the SGD step in their epilogue."""
+        _check(lib().slp_segment_set_fused_update(self._h, int(on)))
 
     def join(self):
         """slp_segment_join: the current stream waits for updates a step with overlap on left running."""

@@ -95,6 +95,10 @@ struct slp_segment {
   // handle's next call that takes a stream (settle), so that the optimiser tail of one segment runs beside whatever
   // the caller enqueues next -- typically the step of another segment.
   bool defer_join, join_pending;
+  // slp_segment_set_fused_update: the weight-gradient product applies the optimiser step in its epilogue; the weight
+  // gradient itself is never stored.
+  bool fused_update;
+  long fused_max_params;                     // layers with more weights than this keep the separate update
   // Small segments are bound by launch latency, not by the GPU: with graphs on, the launch sequence of a step
   // is captured once per (X, targets, batch, loss_out) and replayed as one graph launch afterwards.
   bool use_graph, graph_warm;
@@ -228,11 +232,17 @@ int settle(slp_segment* seg, hipStream_t st) {
 // Weight updates of large layers that run on the side stream, beside the next matrix products, are held to one workgroup
 // per compute unit (256, 512 and 128 were tried: 256 is best, -2 % per step on the comparison and deep configurations).
 constexpr int kSideUpdateWorkgroups = 256;
+// slp_segment_set_fused_update(seg, 2): layers up to this many weights take the update inside their weight-gradient product.
+// Measured on the wide configuration (784-4096-4096-2048 | 2048-4096-4096-47, batch 1024): fusing the layers up to 1 M
+// or 4 M weights is 1-2 % faster than fusing none, fusing the 8 M and 16 M layers as well 2 % and 9 % slower (their
+// epilogues wait on weight and momentum loads that the separate, massively parallel update kernel streams).
+constexpr long kFusedAutoMaxWeights = 1L << 22;
 int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
   // a join cannot be left to a later call while the launches are being captured into a graph
   hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
   if (seg->defer_join && st) HIP_TRY(hipStreamIsCapturing(st, &cap));
   const bool defer = seg->defer_join && cap == hipStreamCaptureStatusNone;
+  bool forked = false;           // whether anything of this step went to the side stream
   for (int l = seg->L; l >= 1; --l) {
     Layer& ly = seg->layers[l - 1];
     if (l > 1) {
@@ -244,8 +254,20 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
     g.B = seg->AT[l - 1]; g.ldb = seg->ldb;
     g.M = ly.N; g.N = ly.K; g.K = batch;
     g.Cf = ly.dW; g.ldc = ly.ldk;
-    int rc = run_gemm(seg, EPI_WGRAD, g, st);
+    const bool fused = seg->fused_update && (long)ly.N * ly.K <= seg->fused_max_params;
+    if (fused) {     // weights, momentum and the derived copies are rewritten by the product's epilogue
+      g.uW = ly.W32; g.uV = ly.vW; g.uW16 = ly.W16; g.uWT = ly.WT; g.ldwt = ly.ldn;
+      g.lr = seg->lr; g.mu = seg->mu;
+    }
+    int rc = run_gemm(seg, fused ? EPI_WGRAD_UPDATE : EPI_WGRAD, g, st);
     if (rc) return rc;
+    if (fused) {
+      // The data gradient of layer l read W_l^T before this product was queued (same stream).  What is left of the
+      // layer is its bias: one small launch, on the caller's stream (nothing worth a second stream).
+      HIP_TRY(launch_layer_update(seg->dtype, nullptr, nullptr, nullptr, ly.N, 0, ly.ldk, nullptr, nullptr, ly.ldn, seg->dZT[l],
+                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, st));
+      continue;
+    }
     // fork: everything layer l still needs (bias gradient, both updates) reads dZ_l^T / dW_l, which are
     // complete here, and writes only layer l's parameters, which nothing below reads in this step
     // without a deferred join the first layer has nothing left in this step to overlap with
@@ -253,6 +275,7 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
     if (us != st) {
       HIP_TRY(hipEventRecord(seg->ev_fork[l - 1], st));
       HIP_TRY(hipStreamWaitEvent(us, seg->ev_fork[l - 1], 0));
+      forked = true;
     }
     // small layers are bound by launch latency: weights and bias in one launch.  Large ones run the bias part as a launch
     // of its own first: inside one launch its long reads of dZ^T slowed the matrix products beside it (measured 1 %).
@@ -266,11 +289,11 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
                                   nullptr, nullptr, nullptr, seg->lr, seg->mu, 0, us != st ? kSideUpdateWorkgroups : 0, us));
     }
   }
-  if (seg->L > 1 || defer) {     // join: later work on the caller's stream sees every update
+  if (forked) {     // join: later work on the caller's stream sees every update
     HIP_TRY(hipEventRecord(seg->ev_join, seg->side));
     if (!defer) HIP_TRY(hipStreamWaitEvent(st, seg->ev_join, 0));
   }
-  seg->join_pending = defer;
+  seg->join_pending = defer && forked;
   return SLP_OK;
 }
 
@@ -300,6 +323,8 @@ int exchange(slp_segment* s, int layer, float* W, float* b, int which, bool set,
   Layer& ly = s->layers[layer];
   float* mats[3] = {ly.W32, ly.dW, ly.vW};
   float* vecs[3] = {ly.b, ly.db, ly.vb};
+  if (W && which == 1 && s->fused_update && (long)ly.N * ly.K <= s->fused_max_params)
+    return fail(SLP_ERR_STATE, "the weight gradient of layer %d is not stored: its update is fused into the product (slp_segment_set_fused_update)", layer);
   if (W) {
     rc = copy_matrix(W, mats[which], ly.N, ly.K, ly.ldk, set, on_device, st);
     if (rc) return rc;
@@ -413,7 +438,7 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
   s->work_bytes = off;
 
   s->side = nullptr; s->ev_join = nullptr;
-  s->defer_join = false; s->join_pending = false;
+  s->defer_join = false; s->join_pending = false; s->fused_update = false; s->fused_max_params = 0;
   s->bound = false; s->have_params = false; s->table = nullptr; s->classes = 0; s->last_batch = 0; s->prof = false;
   s->use_graph = false; s->graph_warm = false; s->graph_tick = 0; s->graph_misses = 0;
   s->partials = nullptr; s->loss_dev = nullptr;
@@ -672,6 +697,20 @@ int slp_segment_set_overlap(slp_segment* seg, int on) {
     HIP_TRY(hipStreamSynchronize(seg->side));
     seg->join_pending = false;
   }
+  return SLP_OK;
+}
+
+int slp_segment_set_fused_update(slp_segment* seg, int on) {
+  int rc = check_seg(seg, false, false);
+  if (rc) return rc;
+  if (on < 0) return fail(SLP_ERR_ARG, "slp_segment_set_fused_update: on must be >= 0 (got %d)", on);
+  if (seg->join_pending) {             // updates of the other kind may still be running on the side stream
+    HIP_TRY(hipStreamSynchronize(seg->side));
+    seg->join_pending = false;
+  }
+  seg->fused_update = on != 0;
+  seg->fused_max_params = on == 1 ? (1L << 62) : (on == 2 ? kFusedAutoMaxWeights : (long)on);
+  drop_graphs(seg);                    // captured steps hold the other launch sequence
   return SLP_OK;
 }
 

@@ -135,6 +135,43 @@ __device__ __forceinline__ void store_quad(const GemmArgs& g, int n, int mb, flo
     if (row < g.M && nb < g.N) *(f32x4_t*)(g.Cf + (size_t)row * g.ldc + nb) = f32x4_t{v[0], v[1], v[2], v[3]};
     return;
   }
+  if (EPI == EPI_WGRAD_UPDATE) {
+    // The optimiser step on the 4 consecutive weights of one output row this lane holds after the transpose
+    // (pad columns hold zeros in every stream and stay zero); then back through the transpose, so that the lane
+    // holds 4 consecutive output rows of one input column: one vector store into the transposed copy.
+    quad_transpose(v, lane);
+    const bool in = row < g.M && nb < g.N;
+    float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (in) {
+      const size_t idx = (size_t)row * g.ldc + nb;
+      const f32x4_t w4 = *(const f32x4_t*)(g.uW + idx);
+      f32x4_t vel = f32x4_t{v[0], v[1], v[2], v[3]};
+      if (g.mu != 0.0f) {
+        vel = g.mu * *(const f32x4_t*)(g.uV + idx) + vel;
+        *(f32x4_t*)(g.uV + idx) = vel;
+      }
+      const f32x4_t wn = w4 - g.lr * vel;
+      *(f32x4_t*)(g.uW + idx) = wn;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = wn[e];
+      if (g.uW16) {
+        bf16x4 h;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = (bf16)w[e];
+        *(bf16x4*)((bf16*)g.uW16 + idx) = h;
+      }
+    }
+    if (g.uWT) {      // (uniform over the launch)
+      quad_transpose(w, lane);
+      if (col_ok && mb < g.M) {     // rows past M inside the vector carry zeros: the pads of the copy stay zero
+        typename Vec4<T>::type o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (T)w[e];
+        *(typename Vec4<T>::type*)((T*)g.uWT + (size_t)n * g.ldwt + mb) = o;
+      }
+    }
+    return;
+  }
   if (mb >= ((g.M + 7) & ~7)) return;       // the same for the whole quad
   if (EPI == EPI_FWD) {
 #pragma unroll
@@ -530,7 +567,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
 #undef SLP_BARRIER
 #undef VMCNT
 
-  if constexpr (EPI == EPI_WGRAD) {
+  if constexpr (EPI == EPI_WGRAD || EPI == EPI_WGRAD_UPDATE) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int n = n0 + wn * WTN + j * 16 + lrow;
@@ -823,12 +860,14 @@ hipError_t launch_epi(int epi, int cfg, const GemmArgs& g, hipStream_t s) {
     switch (epi) {
       case EPI_FWD: return launch_ksplit<T, EPI_FWD>(g, s);
       case EPI_DGRAD: return launch_ksplit<T, EPI_DGRAD>(g, s);
+      case EPI_WGRAD_UPDATE: return launch_ksplit<T, EPI_WGRAD_UPDATE>(g, s);
       default: return launch_ksplit<T, EPI_WGRAD>(g, s);
     }
   }
   switch (epi) {
     case EPI_FWD: return launch_cfg<T, EPI_FWD>(cfg, g, s);
     case EPI_DGRAD: return launch_cfg<T, EPI_DGRAD>(cfg, g, s);
+    case EPI_WGRAD_UPDATE: return launch_cfg<T, EPI_WGRAD_UPDATE>(cfg, g, s);
     default: return launch_cfg<T, EPI_WGRAD>(cfg, g, s);
   }
 }
@@ -852,9 +891,11 @@ hipError_t gemm_configure_all() {
   hipError_t e = configure_epi<bf16, EPI_FWD>();
   if (e == hipSuccess) e = configure_epi<bf16, EPI_DGRAD>();
   if (e == hipSuccess) e = configure_epi<bf16, EPI_WGRAD>();
+  if (e == hipSuccess) e = configure_epi<bf16, EPI_WGRAD_UPDATE>();
   if (e == hipSuccess) e = configure_epi<float, EPI_FWD>();
   if (e == hipSuccess) e = configure_epi<float, EPI_DGRAD>();
   if (e == hipSuccess) e = configure_epi<float, EPI_WGRAD>();
+  if (e == hipSuccess) e = configure_epi<float, EPI_WGRAD_UPDATE>();
   return e;
 }
 
@@ -874,9 +915,13 @@ hipError_t launch_gemm(int dtype, int epi, const GemmArgs& g, hipStream_t s) {
   if (((uintptr_t)g.A | (uintptr_t)g.B) & 15) return hipErrorInvalidValue;
   if (epi == EPI_FWD && !g.bias) return hipErrorInvalidValue;
   if (epi == EPI_WGRAD && !g.Cf) return hipErrorInvalidValue;
-  if (epi != EPI_WGRAD && !g.C && !g.CT) return hipErrorInvalidValue;
+  if (epi == EPI_WGRAD_UPDATE) {
+    if (!g.uW || !g.uV || g.ldc % 4 || (((uintptr_t)g.uW | (uintptr_t)g.uV | (uintptr_t)g.uW16 | (uintptr_t)g.uWT) & 15)) return hipErrorInvalidValue;
+    if (g.uWT && g.ldwt % kLdAlign) return hipErrorInvalidValue;
+  }
+  if (epi != EPI_WGRAD && epi != EPI_WGRAD_UPDATE && !g.C && !g.CT) return hipErrorInvalidValue;
   // outputs are written as 16-byte vectors
-  if (epi != EPI_WGRAD && ((g.C && (g.ldc % kLdAlign || ((uintptr_t)g.C & 15))) || (g.CT && (g.ldct % kLdAlign || ((uintptr_t)g.CT & 15)))))
+  if (epi != EPI_WGRAD && epi != EPI_WGRAD_UPDATE && ((g.C && (g.ldc % kLdAlign || ((uintptr_t)g.C & 15))) || (g.CT && (g.ldct % kLdAlign || ((uintptr_t)g.CT & 15)))))
     return hipErrorInvalidValue;
   if (epi == EPI_WGRAD && (g.ldc % 4 || ((uintptr_t)g.Cf & 15))) return hipErrorInvalidValue;
   const int cfg = pick_cfg(g.M, g.N);
@@ -885,7 +930,7 @@ hipError_t launch_gemm(int dtype, int epi, const GemmArgs& g, hipStream_t s) {
   // tile columns).  8 is best everywhere except the weight gradient of a tall output (64 or more tile rows), whose
   // float32 rows are written faster when the concurrent tiles are wider than tall: measured 3.61 -> 3.47 ms on
   // 16384x16384x8192 and 1.90 -> 1.82 ms on 16384x8192x8192, no gain or a loss on every other shape tried.
-  h.group_m = (epi == EPI_WGRAD && cfg == 0 && (g.M + 255) / 256 >= 64) ? 4 : kGroupM;
+  h.group_m = ((epi == EPI_WGRAD || epi == EPI_WGRAD_UPDATE) && cfg == 0 && (g.M + 255) / 256 >= 64) ? 4 : kGroupM;
   // Big bf16 products whose tile grid divides into 16 x 16 regions take the region walk instead: equal or better than
   // either group height on every shape tried (+1-4 %; +14 % on the short contraction of a first layer, K = 784).
   if (cfg == 0 && dtype == 1 && ((g.M + 255) / 256) % 16 == 0 && ((g.N + 255) / 256) % 16 == 0) h.group_m = kRegionWalk;

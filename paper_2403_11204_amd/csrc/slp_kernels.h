@@ -27,7 +27,7 @@ inline int internal_ld(int width, int esize) {
   return ld;
 }
 
-enum Epilogue { EPI_FWD = 0, EPI_DGRAD = 1, EPI_WGRAD = 2 };
+enum Epilogue { EPI_FWD = 0, EPI_DGRAD = 1, EPI_WGRAD = 2, EPI_WGRAD_UPDATE = 3 };
 
 // C[m][n] = sum_k A[m][k] * B[n][k]  ("NT": both operands contraction-contiguous).
 struct GemmArgs {
@@ -47,6 +47,13 @@ struct GemmArgs {
   const void* maskT;  // [N][ldmask], element type T
   int ldmask;
   float* Cf;       // [M][ldc] float32
+  // EPI_WGRAD_UPDATE: the gradient never goes to memory; the epilogue applies the optimiser step to the tile it holds
+  // (paper Sec. 3: SGD with momentum), v = mu v + acc; w -= lr v, on the float32 master weights uW and momentum uV
+  // (both [M][ldc]), and rewrites the derived copies uW16 (bf16 [M][ldc], may be null) and uWT ([N][ldwt], element
+  // type T, may be null).  Cf is not used.
+  float* uW; float* uV; void* uW16; void* uWT;
+  int ldwt;
+  float lr, mu;
 };
 
 // dtype: 0 = float32 operands, 1 = bf16 operands (float32 accumulation in both).

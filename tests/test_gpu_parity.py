@@ -127,7 +127,7 @@ def compare_rows_without_ties(out, free, acts, dzs, tol):
     return compared
 
 
-def check_step(g, o, X, y, table_np, dtype, steps=1, check_internals=True, tie_cap=1e-4):
+def check_step(g, o, X, y, table_np, dtype, steps=1, check_internals=True, tie_cap=1e-4, stored_dW=True):
     tol = TOL[dtype]
     B = X.shape[0]
     Xd, Xv = as_input(X, dtype)
@@ -165,8 +165,11 @@ def check_step(g, o, X, y, table_np, dtype, steps=1, check_internals=True, tie_c
             dz_got = to_np(g.get_activation(l, B, kind=1)).astype(np.float64)
             assert rel_err(dz_got, dz_ref) <= tol, ("dZ", l)
         for l in range(o.L):
-            dW, db = g.get_grads(l)
-            assert rel_err(to_np(dW), out["dW"][l]) <= tol, ("dW", l)
+            if stored_dW:
+                dW, db = g.get_grads(l)
+                assert rel_err(to_np(dW), out["dW"][l]) <= tol, ("dW", l)
+            else:       # fused update: the weight gradient exists only inside the product (checked through vW and W below)
+                db = g.get_bias_grad(l)
             assert rel_err(to_np(db), out["db"][l]) <= tol, ("db", l)
     for l in range(o.L):
         W, b = g.get_params(l)
@@ -256,6 +259,35 @@ def test_one_step(case, dtype):
 
 
 @pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_one_step_with_the_update_inside_the_weight_gradient_product(case, dtype):
+    # the same cases with the optimiser step applied in the epilogue of the weight-gradient product: parameters,
+    # momentum (= the weight gradient after a first step from zero momentum) and everything else against the oracle
+    name, widths, act, loss, B, dist, classes = case
+    X, y, table = case_data(widths, loss, B, dist, classes, seed=1)
+    g, o = make_pair(widths, act, loss, dtype, max_batch=B, lr=0.01, mom=0.9, wseed=3)
+    g.set_fused_update(True)
+    check_step(g, o, X, y, table, dtype, stored_dW=False)
+    with pytest.raises(api.SlpError) as e:
+        g.get_grads(0)
+    assert e.value.code == -5
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+@pytest.mark.parametrize("mom", [0.0, 0.9])
+def test_several_fused_steps_then_back_to_the_separate_update(dtype, mom):
+    # five steps with the fused update (ragged shapes: pads of every derived copy must stay zero for the next products),
+    # then the switch goes off and two ordinary steps follow on the same handle
+    widths = [70, 130, 61, 33]
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, dtype, max_batch=90, lr=0.02, mom=mom, wseed=6)
+    X, y, table = case_data(widths, api.MSE_SIL, 90, api.UNIFORM01, 20, seed=4)
+    g.set_fused_update(True)
+    check_step(g, o, X, y, table, dtype, steps=5, check_internals=(dtype == api.F32), stored_dW=False)
+    g.set_fused_update(False)
+    check_step(g, o, X[:77], y[:77], table, dtype, steps=2, check_internals=False)
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
 def test_plain_sgd_and_smaller_batches_on_one_handle(dtype):
     # momentum 0 path; then a shorter, ragged batch on the same handle (stale pad columns must not leak)
     widths = [48, 96, 40]
@@ -309,6 +341,32 @@ def test_wide_bf16_config_one_step():
     XB = orng.make_segment_inputs(5, table, y, 0, 0.05)
     g, o = make_pair([2048, 4096, 4096, 47], api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, api.BF16, 1024, 0.01, 0.9, wseed=8)
     check_step(g, o, XB, y, None, api.BF16)
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+def test_fused_update_by_layer_size(dtype):
+    # rule 2: the 2100 x 2100 layer (4.41 M weights) keeps the separate update and its stored gradient, the two
+    # small layers are updated inside their products
+    widths, B = [64, 2100, 2100, 32], 128
+    X, y, table = case_data(widths, api.MSE_SIL, B, api.UNIFORM_PM1, 20, seed=4)
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, dtype, max_batch=B, lr=0.02, mom=0.9, wseed=6)
+    g.set_fused_update(2)
+    check_step(g, o, X, y, table, dtype, steps=2, stored_dW=False)
+    dW, _ = g.get_grads(1)                       # the large layer's gradient is there
+    assert float(dW.abs().max()) > 0
+    for l in (0, 2):
+        with pytest.raises(api.SlpError):
+            g.get_grads(l)
+
+
+def test_wide_bf16_config_one_fused_step():
+    # the wide configuration's first segment (784-4096-4096-2048, batch 1024, bf16): its weight gradients run on the
+    # 128x128 and 256x256 tiles, here with the update in their epilogues
+    widths, B = [784, 4096, 4096, 2048], 1024
+    X, y, table = case_data(widths, api.MSE_SIL, B, api.BINARY_PM1, 47, seed=1)
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, api.BF16, max_batch=B, lr=0.01, mom=0.9, wseed=3)
+    g.set_fused_update(True)
+    check_step(g, o, X, y, table, api.BF16, stored_dW=False)
 
 
 def test_tiny_config_epoch_loss_curve():
