@@ -276,6 +276,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="configs 0-2: launch every kernel of a step instead of replaying graphs")
     ap.add_argument("--fused", type=int, nargs="?", const=1, default=0, help="apply the update in the epilogue of the weight-gradient products")
     ap.add_argument("--unfused", action="store_true", help="configs 0-2 and 5: separate update launches instead of the fused update")
+    ap.add_argument("--events-apart", action="store_true",
+                    help="time the steps without per-launch events and the matrix products in a second pass (as the graph configs do)")
     ap.add_argument("--serial", action="store_true", help="config 3: run the four segments one after another on one stream")
     ap.add_argument("--no-overlap", action="store_true",
                     help="end every step by waiting for its parameter updates (slp_segment_set_overlap off)")
@@ -320,6 +322,10 @@ def main():
             wall_ms, ev_ms, _ = time_workload(segs, inputs, ys, False, steps, warmup, profile=False)
             prof_steps = max(steps // 4, 10)
             _, _, prof = time_workload(segs, inputs, ys, False, prof_steps, 2)
+    elif args.events_apart:
+        wall_ms, ev_ms, _ = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup, profile=False)
+        prof_steps = max(steps // 2, 5)
+        _, _, prof = time_workload(segs, inputs, ys, cfg["streams"], prof_steps, 2)
     else:
         prof_steps = steps
         wall_ms, ev_ms, prof = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup)

@@ -153,7 +153,7 @@ int slp_segment_set_labels(slp_segment* seg, const float* table /*device*/, int 
  * for the batch X[batch][widths[0]] (dense, handle dtype, device) with class ids
  * targets[batch] (int32, device).  For SLP_MSE_SIL the ids select rows of the bound
  * label table; for SLP_SOFTMAX_XENT they are the classes (< last width).  Ids are
- * clamped into range on the device.  If loss_out is not NULL the mean loss of the
+ * clamped into range on the device and counted (slp_segment_target_errors).  If loss_out is not NULL the mean loss of the
  * batch (before the update) is written there (float32, device).  No host
  * synchronisation; X and targets are only read.  batch may be any value in
  * [1, max_batch]; the means run over the batch actually passed.
@@ -162,6 +162,13 @@ int slp_segment_set_labels(slp_segment* seg, const float* table /*device*/, int 
  * SLP_ERR_DEVICE (a launch failed). */
 int slp_segment_step(slp_segment* seg, const void* X /*device*/, const int32_t* targets /*device*/, int batch,
                      float* loss_out /*device, may be NULL*/, slp_stream stream);
+
+/* Class ids are the caller's data: an id outside its range (rows of the label table for SLP_MSE_SIL, the last width
+ * for SLP_SOFTMAX_XENT) is clamped into range on the device so that nothing is read out of bounds, and the row is
+ * COUNTED: *count_out (host) receives the number of such rows seen by the handle's loss kernels since slp_segment_bind.
+ * A non-zero count means steps trained on wrong targets.  Synchronises `stream`.  Errors: SLP_ERR_ARG (null),
+ * SLP_ERR_STATE (not bound), SLP_ERR_DEVICE. */
+int slp_segment_target_errors(slp_segment* seg, int64_t* count_out /*host*/, slp_stream stream);
 
 /* Forward only (Sec. 2: the stored response of the left partition; joining the
  * partitions): out[batch][last width], dense, handle dtype, device.  Parameters

@@ -66,6 +66,7 @@ def lib():
         "slp_segment_set_graph": (i32, [vp, i32]),
         "slp_segment_set_overlap": (i32, [vp, i32]),
         "slp_segment_set_fused_update": (i32, [vp, i32]),
+        "slp_segment_target_errors": (i32, [vp, ctypes.POINTER(i64), vp]),
         "slp_segment_join": (i32, [vp, vp]),
         "slp_segment_profile_read": (i32, [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]),
         "slp_probe_mfma_rate": (i32, [i32, i32, vp, sz, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), vp]),
@@ -87,7 +88,7 @@ EXPORTS = ["slp_last_error", "slp_make_synthetic_labels", "slp_make_segment_inpu
            "slp_segment_step", "slp_segment_forward", "slp_segment_input_grad", "slp_segment_step_external",
            "slp_segment_profile_enable", "slp_segment_profile_read", "slp_probe_mfma_rate",
            "slp_segment_set_graph", "slp_segment_set_overlap", "slp_segment_join", "slp_count_correct", "slp_mean_loss",
-           "slp_count_correct_static", "slp_segment_set_fused_update"]
+           "slp_count_correct_static", "slp_segment_set_fused_update", "slp_segment_target_errors"]
 
 
 def _check(code):
@@ -284,6 +285,12 @@ class Segment:
     def set_fused_update(self, on=True):
         """slp_segment_set_fused_update: the weight-gradient products apply the SGD step in their epilogue."""
         _check(lib().slp_segment_set_fused_update(self._h, int(on)))
+
+    def target_errors(self):
+        """slp_segment_target_errors: rows with an out-of-range class id seen since bind (synchronises the stream)."""
+        n = ctypes.c_int64()
+        _check(lib().slp_segment_target_errors(self._h, ctypes.byref(n), _stream()))
+        return n.value
 
     def join(self):
         """slp_segment_join: the current stream waits for updates a step with overlap on left running."""

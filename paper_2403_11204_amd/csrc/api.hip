@@ -74,9 +74,10 @@ struct slp_segment {
   // workspace offsets / pointers, index = layer 0..L
   std::vector<size_t> oA, oAT, odZ, odZT;
   std::vector<void*> A, AT, dZ, dZT;
-  size_t oPartials, oLoss;
+  size_t oPartials, oLoss, oBadIds;
   int n_partials;
   float *partials, *loss_dev;
+  unsigned* bad_ids;                         // rows whose class id was out of range, counted by the loss kernels
   bool bound, have_params;
   bool input_grad;                           // keeps W_1^T and a dZ_0 buffer so that d loss / d input can be formed
   const float* table;
@@ -187,11 +188,11 @@ int loss_and_output_grad(slp_segment* seg, const int32_t* targets, int batch, fl
   const int L = seg->L, D = seg->widths[L];
   if (seg->loss == SLP_MSE_SIL) {
     HIP_TRY(launch_mse_loss_grad(seg->dtype, seg->A[L], seg->ldw[L], targets, seg->table, seg->classes, batch, D,
-                                 relu_on(seg, L) ? 1 : 0, seg->dZ[L], seg->dZT[L], seg->ldb, seg->partials, st));
+                                 relu_on(seg, L) ? 1 : 0, seg->dZ[L], seg->dZT[L], seg->ldb, seg->partials, seg->bad_ids, st));
     HIP_TRY(launch_reduce_loss(seg->partials, mse_partial_count(batch, D), 1.0 / ((double)batch * D), seg->loss_dev, loss_out, st));
   } else {
     HIP_TRY(launch_xent_loss_grad(seg->dtype, seg->A[L], seg->ldw[L], targets, batch, D, relu_on(seg, L) ? 1 : 0,
-                                  seg->dZ[L], seg->partials, st));
+                                  seg->dZ[L], seg->partials, seg->bad_ids, st));
     HIP_TRY(launch_copy_transpose(seg->dtype, seg->dZ[L], seg->ldw[L], batch, D, nullptr, 0, seg->dZT[L], seg->ldb, 1,
                                   nullptr, 0, st));
     HIP_TRY(launch_reduce_loss(seg->partials, batch, 1.0 / (double)batch, seg->loss_dev, loss_out, st));
@@ -435,13 +436,14 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
   s->n_partials = loss == SLP_MSE_SIL ? mse_partial_count(s->max_batch, s->widths[s->L]) : s->max_batch;
   s->oPartials = take((size_t)s->n_partials * 4);
   s->oLoss = take(4);
+  s->oBadIds = take(4);
   s->work_bytes = off;
 
   s->side = nullptr; s->ev_join = nullptr;
   s->defer_join = false; s->join_pending = false; s->fused_update = false; s->fused_max_params = 0;
   s->bound = false; s->have_params = false; s->table = nullptr; s->classes = 0; s->last_batch = 0; s->prof = false;
   s->use_graph = false; s->graph_warm = false; s->graph_tick = 0; s->graph_misses = 0;
-  s->partials = nullptr; s->loss_dev = nullptr;
+  s->partials = nullptr; s->loss_dev = nullptr; s->bad_ids = nullptr;
   *out = s;
   return SLP_OK;
 }
@@ -497,6 +499,7 @@ int slp_segment_bind(slp_segment* seg, void* params, size_t params_bytes, void* 
   }
   seg->partials = (float*)at(seg->oPartials);
   seg->loss_dev = (float*)at(seg->oLoss);
+  seg->bad_ids = (unsigned*)at(seg->oBadIds);
   if (!seg->side) {     // host-side objects only; default priority
     HIP_TRY(hipStreamCreateWithFlags(&seg->side, hipStreamNonBlocking));
     HIP_TRY(hipEventCreateWithFlags(&seg->ev_join, hipEventDisableTiming));
@@ -676,6 +679,18 @@ int slp_segment_step(slp_segment* seg, const void* X, const int32_t* targets, in
     seg->graphs.push_back(sg);
   }
   HIP_TRY(hipGraphLaunch(sg.exec, st));
+  return SLP_OK;
+}
+
+int slp_segment_target_errors(slp_segment* seg, int64_t* count_out, slp_stream stream) {
+  int rc = check_seg(seg, true, false);
+  if (rc) return rc;
+  if (!count_out) return fail(SLP_ERR_ARG, "count_out is NULL");
+  hipStream_t st = (hipStream_t)stream;
+  unsigned n = 0;
+  HIP_TRY(hipMemcpyAsync(&n, seg->bad_ids, sizeof(n), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  *count_out = (int64_t)n;
   return SLP_OK;
 }
 

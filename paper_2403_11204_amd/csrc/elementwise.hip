@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void mse_loss_grad_kernel(const T* __restrict_
                                                             const float* __restrict__ table, int classes, int B, int D,
                                                             int relu_last,
                                                             float scale, T* __restrict__ dZ, T* __restrict__ dZT, int ldt,
-                                                            float* __restrict__ partials) {
+                                                            float* __restrict__ partials, unsigned* __restrict__ bad_ids) {
   typedef typename Vec16<T>::type vec_t;
   typedef __attribute__((ext_vector_type(4))) float f32x4;
   constexpr int V = Vec16<T>::n, CPR = 64 / V, ITEMS = 64 * CPR / 256;
@@ -165,6 +165,7 @@ __global__ __launch_bounds__(256) void mse_loss_grad_kernel(const T* __restrict_
     if (m < B && i < D) {
       const vec_t av = *(const vec_t*)(AL + (size_t)m * ld + i);     // a chunk that straddles D reads pad zeros
       const int cls = min(max(y[m], 0), classes - 1);                 // ids are the caller's; never index outside the table
+      if (cls != y[m] && blockIdx.x == 0 && ch == 0) atomicAdd(bad_ids, 1u);   // once per row; rare, and the count is an integer
       const float* trow = table + (size_t)cls * D + i;
       float tv[V];
       if (table_vec && i + V <= D) {
@@ -204,7 +205,8 @@ __global__ __launch_bounds__(256) void mse_loss_grad_kernel(const T* __restrict_
 template <typename T>
 __global__ __launch_bounds__(256) void xent_loss_grad_kernel(const T* __restrict__ ZL, int ld, const int32_t* __restrict__ y,
                                                              int B, int C, int relu_last, float inv_b,
-                                                             T* __restrict__ dZ, float* __restrict__ row_loss) {
+                                                             T* __restrict__ dZ, float* __restrict__ row_loss,
+                                                             unsigned* __restrict__ bad_ids) {
   const int lane = threadIdx.x & 63;
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (m < B) {
@@ -217,6 +219,7 @@ __global__ __launch_bounds__(256) void xent_loss_grad_kernel(const T* __restrict
     sum = wave_sum(sum);
     const float lse = mx + logf(sum);
     const int cls = min(max(y[m], 0), C - 1);
+    if (lane == 0 && cls != y[m]) atomicAdd(bad_ids, 1u);
     if (lane == 0) row_loss[m] = lse - to_f32(z[cls]);
     T* g = dZ + (size_t)m * ld;
     for (int c = lane; c < C; c += 64) {
@@ -445,26 +448,27 @@ hipError_t launch_copy_transpose(int dtype, const void* in, int ldin, int R, int
 int mse_partial_count(int B, int D) { return ((D + 63) / 64) * ((B + 63) / 64); }
 
 hipError_t launch_mse_loss_grad(int dtype, const void* AL, int ld, const int32_t* y, const float* table, int classes,
-                                int B, int D, int relu_last, void* dZ, void* dZT, int ldt, float* partials, hipStream_t s) {
+                                int B, int D, int relu_last, void* dZ, void* dZT, int ldt, float* partials, unsigned* bad_ids,
+                                hipStream_t s) {
   dim3 grid((D + 63) / 64, (B + 63) / 64);
   const float scale = (float)(2.0 / ((double)B * (double)D));
   if (dtype == 1)
     mse_loss_grad_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)AL, ld, y, table, classes, B, D, relu_last, scale, (bf16*)dZ,
-                                                    (bf16*)dZT, ldt, partials);
+                                                    (bf16*)dZT, ldt, partials, bad_ids);
   else
     mse_loss_grad_kernel<float><<<grid, 256, 0, s>>>((const float*)AL, ld, y, table, classes, B, D, relu_last, scale, (float*)dZ,
-                                                     (float*)dZT, ldt, partials);
+                                                     (float*)dZT, ldt, partials, bad_ids);
   return hipGetLastError();
 }
 
 hipError_t launch_xent_loss_grad(int dtype, const void* ZL, int ld, const int32_t* y, int B, int C, int relu_last,
-                                 void* dZ, float* partials, hipStream_t s) {
+                                 void* dZ, float* partials, unsigned* bad_ids, hipStream_t s) {
   const int grid = (B + 3) / 4;
   const float inv_b = (float)(1.0 / (double)B);
   if (dtype == 1)
-    xent_loss_grad_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)ZL, ld, y, B, C, relu_last, inv_b, (bf16*)dZ, partials);
+    xent_loss_grad_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)ZL, ld, y, B, C, relu_last, inv_b, (bf16*)dZ, partials, bad_ids);
   else
-    xent_loss_grad_kernel<float><<<grid, 256, 0, s>>>((const float*)ZL, ld, y, B, C, relu_last, inv_b, (float*)dZ, partials);
+    xent_loss_grad_kernel<float><<<grid, 256, 0, s>>>((const float*)ZL, ld, y, B, C, relu_last, inv_b, (float*)dZ, partials, bad_ids);
   return hipGetLastError();
 }
 

@@ -783,13 +783,12 @@ int pick_cfg(int M, int N) {
 template <typename T, int BM, int BN, int EPI, int NW, int NS>
 hipError_t configure_one() {
   constexpr int smem = NS * (BM + BN) * 128;
-  static bool configured = false;   // one attribute call per instantiation
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_nt_kernel<T, BM, BN, EPI, NW, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  return hipSuccess;
+  static std::once_flag once;       // one attribute call per instantiation, also when two host threads launch first together
+  static hipError_t result = hipSuccess;
+  std::call_once(once, [] {
+    result = hipFuncSetAttribute((const void*)gemm_nt_kernel<T, BM, BN, EPI, NW, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  });
+  return result;
 }
 
 template <typename T, int BM, int BN, int EPI, int NW, int NS>
@@ -808,13 +807,12 @@ constexpr int kBigSmem = 2 * 512 * 128;
 
 template <int EPI>
 hipError_t configure_big() {
-  static bool configured = false;   // one attribute call per instantiation
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_nt_big_kernel<EPI, kBigWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigSmem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  return hipSuccess;
+  static std::once_flag once;
+  static hipError_t result = hipSuccess;
+  std::call_once(once, [] {
+    result = hipFuncSetAttribute((const void*)gemm_nt_big_kernel<EPI, kBigWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigSmem);
+  });
+  return result;
 }
 
 template <int EPI>

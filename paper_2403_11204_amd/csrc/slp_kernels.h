@@ -67,17 +67,19 @@ const char* gemm_config_name(int dtype, int M, int N, int K);
 hipError_t launch_copy_transpose(int dtype, const void* in, int ldin, int R, int C, void* out, int ldo, void* outT,
                                  int ldt, int pad_t, const void* mask, int ldmask, hipStream_t s);
 
+// Both loss kernels clamp a class id outside its range (memory safety) and count such rows into *bad_ids.
 // Mean-squared-error loss against table[y[m]] and its gradient w.r.t. the
 // pre-activation (ReLU mask applied when relu_last).  Writes dZ (row-major, optional),
 // dZT (transposed, zero-filled pads) and one partial sum per block.
 hipError_t launch_mse_loss_grad(int dtype, const void* AL, int ld, const int32_t* y, const float* table, int classes,
-                                int B, int D, int relu_last, void* dZ, void* dZT, int ldt, float* partials, hipStream_t s);
+                                int B, int D, int relu_last, void* dZ, void* dZT, int ldt, float* partials, unsigned* bad_ids,
+                                hipStream_t s);
 int mse_partial_count(int B, int D);
 
 // Softmax cross-entropy per row: dZ[m][c] = (softmax - onehot)/B (zeroed where the
 // last layer's ReLU is inactive when relu_last), per-row loss to partials[m].
 hipError_t launch_xent_loss_grad(int dtype, const void* ZL, int ld, const int32_t* y, int B, int C, int relu_last,
-                                 void* dZ, float* partials, hipStream_t s);
+                                 void* dZ, float* partials, unsigned* bad_ids, hipStream_t s);
 
 // out0[0] (and out1[0] if not null) = scale * sum(partials[0..n)), fixed summation order.
 hipError_t launch_reduce_loss(const float* partials, int n, double scale, float* out0, float* out1, hipStream_t s);

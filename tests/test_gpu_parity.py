@@ -494,6 +494,28 @@ def test_step_argument_errors():
     assert e.value.code == -5
 
 
+@pytest.mark.parametrize("loss", [api.MSE_SIL, api.SOFTMAX_XENT])
+def test_out_of_range_class_ids_are_clamped_and_counted(loss):
+    # ids are the caller's data: the kernels clamp them (nothing is read out of bounds) and count the rows
+    classes, B = 10, 200
+    widths = [12, 20, 16] if loss == api.MSE_SIL else [12, 20, classes]
+    act = api.RELU_ALL if loss == api.MSE_SIL else api.RELU_HIDDEN_IDENTITY_LAST
+    X, y, table = case_data(widths, loss, B, api.UNIFORM_PM1, classes, seed=5)
+    g, o = make_pair(widths, act, loss, api.F32, max_batch=B, lr=0.01, mom=0.0, wseed=5)
+    if table is not None:
+        g.set_labels(torch.from_numpy(table).to(DEV))
+    Xd, Xv = as_input(X, api.F32)
+    g.step(Xd, torch.from_numpy(y).to(DEV))
+    assert g.target_errors() == 0
+    bad = y.copy()
+    bad[[3, 77, 199]] = [classes, -1, 1 << 20]
+    loss_g = float(g.step(Xd, torch.from_numpy(bad).to(DEV)).item())
+    assert g.target_errors() == 3
+    o.step(Xv, y, table)                                               # the first, valid step
+    ref = o.step(Xv, np.clip(bad, 0, classes - 1), table)["loss"]     # what the clamped ids mean
+    assert abs(loss_g - ref) <= 1e-5 * ref
+
+
 def test_mfma_probe_reports_a_rate_below_the_published_peak():
     for dtype, peak in ((api.BF16, 2516.6), (api.F32, 157.3)):
         tf, ms = api.probe_mfma_rate(dtype, iters=2000)
