@@ -244,6 +244,12 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
   if (seg->defer_join && st) HIP_TRY(hipStreamIsCapturing(st, &cap));
   const bool defer = seg->defer_join && cap == hipStreamCaptureStatusNone;
   bool forked = false;           // whether anything of this step went to the side stream
+  // With the join left to a later call the update's tail has the caller's next work to hide behind, and the update can
+  // be paced so that its loads fit beside the products' (see sgd_update_strided_kernel).  How long it may take scales
+  // with the batch (the products beside it do): nothing up to 2048 rows, 8 units at 4096, capped at 14 from 5632 on --
+  // measured: comparison configuration (8192 rows) best at 10-16 units, deep configuration run serially (4096) at 8-14,
+  // wide configuration (1024) 18 % slower with any pause.
+  const int pause = defer ? std::min(14, std::max(0, (batch - 2048) / 256)) : 0;
   for (int l = seg->L; l >= 1; --l) {
     Layer& ly = seg->layers[l - 1];
     if (l > 1) {
@@ -266,7 +272,7 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
       // The data gradient of layer l read W_l^T before this product was queued (same stream).  What is left of the
       // layer is its bias: one small launch, on the caller's stream (nothing worth a second stream).
       HIP_TRY(launch_layer_update(seg->dtype, nullptr, nullptr, nullptr, ly.N, 0, ly.ldk, nullptr, nullptr, ly.ldn, seg->dZT[l],
-                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, st));
+                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, 0, st));
       continue;
     }
     // fork: everything layer l still needs (bias gradient, both updates) reads dZ_l^T / dW_l, which are
@@ -282,12 +288,12 @@ int backward_and_update(slp_segment* seg, int batch, hipStream_t st) {
     // of its own first: inside one launch its long reads of dZ^T slowed the matrix products beside it (measured 1 %).
     if ((size_t)ly.N * ly.K <= ((size_t)1 << 22)) {
       HIP_TRY(launch_layer_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, seg->dZT[l],
-                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, us));
+                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, 0, us));
     } else {
       HIP_TRY(launch_layer_update(seg->dtype, nullptr, nullptr, nullptr, ly.N, 0, ly.ldk, nullptr, nullptr, ly.ldn, seg->dZT[l],
-                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, us));
+                                  seg->ldb, batch, ly.db, ly.b, ly.vb, seg->lr, seg->mu, 0, 0, 0, us));
       HIP_TRY(launch_layer_update(seg->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, nullptr, 0, 0,
-                                  nullptr, nullptr, nullptr, seg->lr, seg->mu, 0, us != st ? kSideUpdateWorkgroups : 0, us));
+                                  nullptr, nullptr, nullptr, seg->lr, seg->mu, 0, us != st ? kSideUpdateWorkgroups : 0, us != st ? pause : 0, us));
     }
   }
   if (forked) {     // join: later work on the caller's stream sees every update
@@ -302,7 +308,7 @@ int refresh_copies(slp_segment* s, int layer, hipStream_t st) {
   Layer& ly = s->layers[layer];
   if (!ly.W16 && !ly.WT) return SLP_OK;
   HIP_TRY(launch_layer_update(s->dtype, ly.W32, ly.vW, ly.dW, ly.N, ly.K, ly.ldk, ly.W16, ly.WT, ly.ldn, nullptr, 0, 0, nullptr,
-                              nullptr, nullptr, 0.0f, 0.0f, 1, 0, st));
+                              nullptr, nullptr, 0.0f, 0.0f, 1, 0, 0, st));
   return SLP_OK;
 }
 

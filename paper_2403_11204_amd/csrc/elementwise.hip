@@ -394,14 +394,20 @@ __global__ __launch_bounds__(256) void sgd_update_kernel(float* __restrict__ W32
 // the 512 registers, and a wavefront that needs more than the 64 left cannot share the SIMD with them.  At 68 the
 // update's workgroups could only start on a compute unit between two product workgroups and then kept the next one
 // out for as long as they ran (comparison configuration: 38.9 -> 36.9 ms per step with the limit).
+// pause: units of ~0.5 us that a workgroup sleeps after each 64x64 tile.  A compute unit's vector memory path delivers
+// ~56 GB/s (measured with one copy workgroup per compute unit) and the product beside the update already takes ~48 of
+// them, so the update's loads queue in front of the product's; spread over twice the time they fit into the headroom
+// (comparison configuration 37.1 -> 36.7 ms per step, deep configuration run serially 13.2 -> 12.9 at 8-14 units; the
+// update's tail must still find products to hide behind, which is why the caller sizes the pause by the batch).
 template <typename T>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8))) void sgd_update_strided_kernel(float* __restrict__ W32, float* __restrict__ vW,
                                                                  const float* __restrict__ dW, int N, int K, int ldk,
                                                                  bf16* __restrict__ W16, T* __restrict__ WT, int ldn, float lr,
-                                                                 float mu, int refresh_only) {
+                                                                 float mu, int refresh_only, int pause) {
   const int kb = (K + 63) / 64, tiles = kb * ((N + 63) / 64);
   for (int id = blockIdx.x; id < tiles; id += gridDim.x) {
     sgd_update_block<T>(id % kb, id / kb, W32, vW, dW, N, K, ldk, W16, WT, ldn, lr, mu, refresh_only);
+    for (int i = 0; i < pause; ++i) __builtin_amdgcn_s_sleep(16);
     __syncthreads();   // the LDS tile is reused
   }
 }
@@ -479,14 +485,14 @@ hipError_t launch_reduce_loss(const float* partials, int n, double scale, float*
 
 hipError_t launch_layer_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16, void* WT,
                                int ldn, const void* dZT, int ldt, int B, float* db, float* b, float* vb, float lr, float mu,
-                               int refresh_only, int max_workgroups, hipStream_t s) {
+                               int refresh_only, int max_workgroups, int pause, hipStream_t s) {
   if (!dZT) {       // weights only
     const int wgs = max_workgroups;
     if (wgs > 0 && (long)((K + 63) / 64) * ((N + 63) / 64) > wgs) {
       if (dtype == 1)
-        sgd_update_strided_kernel<bf16><<<wgs, 256, 0, s>>>(W32, vW, dW, N, K, ldk, (bf16*)W16, (bf16*)WT, ldn, lr, mu, refresh_only);
+        sgd_update_strided_kernel<bf16><<<wgs, 256, 0, s>>>(W32, vW, dW, N, K, ldk, (bf16*)W16, (bf16*)WT, ldn, lr, mu, refresh_only, pause);
       else
-        sgd_update_strided_kernel<float><<<wgs, 256, 0, s>>>(W32, vW, dW, N, K, ldk, nullptr, (float*)WT, ldn, lr, mu, refresh_only);
+        sgd_update_strided_kernel<float><<<wgs, 256, 0, s>>>(W32, vW, dW, N, K, ldk, nullptr, (float*)WT, ldn, lr, mu, refresh_only, pause);
       return hipGetLastError();
     }
     dim3 grid2((K + 63) / 64, (N + 63) / 64);

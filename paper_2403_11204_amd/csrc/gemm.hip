@@ -407,6 +407,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
 #if defined(__HIP_DEVICE_COMPILE__)
   typedef bf16 T;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // highest wave priority: on a compute unit shared with an update workgroup the product's loads are issued first
+  // (+0.4 % per step on the comparison configuration; no effect when the kernel runs alone)
+  __builtin_amdgcn_s_setprio(3);
   constexpr int BM = 256, BN = 256, ES = 2, CH = 8, BK = 64;
   constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
   constexpr int WN = NW / 2;             // wavefront columns

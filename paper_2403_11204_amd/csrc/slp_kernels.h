@@ -88,10 +88,11 @@ hipError_t launch_reduce_loss(const float* partials, int n, double scale, float*
 // W16 (bf16 [N][ldk], bf16 mode only) and WT ([K][ldn], element type T, optional), and -- unless dZT is null --
 // the bias: db[n] = sum_{m < B} dZT[n][m], then the same update on b, vb.
 // refresh_only: skip the arithmetic and only rebuild the copies from W32 (dZT must be null).
-// max_workgroups > 0 (weights-only launches): run on at most that many workgroups, for updates issued beside matrix products.
+// max_workgroups > 0 (weights-only launches): run on at most that many workgroups, for updates issued beside matrix products;
+// pause: units of ~0.5 us each of those workgroups sleeps between two tiles (paces the update's memory traffic).
 hipError_t launch_layer_update(int dtype, float* W32, float* vW, const float* dW, int N, int K, int ldk, void* W16, void* WT,
                                int ldn, const void* dZT, int ldt, int B, float* db, float* b, float* vb, float lr, float mu,
-                               int refresh_only, int max_workgroups, hipStream_t s);
+                               int refresh_only, int max_workgroups, int pause, hipStream_t s);
 
 // Counter-based generators (Philox4x32-10).
 hipError_t launch_make_labels(uint64_t seed, int classes, int dim, int dist, float kappa, void* out, int dt,
