@@ -39,18 +39,18 @@ template <typename T> struct Vec16;
 template <> struct Vec16<bf16> { typedef __attribute__((ext_vector_type(8))) __bf16 type; static constexpr int n = 8; };
 template <> struct Vec16<float> { typedef __attribute__((ext_vector_type(4))) float type; static constexpr int n = 4; };
 
-template <typename T>
+template <typename T, int TILE = 64>
 __device__ __forceinline__ int tile_slot(int row, int chunk) {     // position of a chunk in the LDS tile, in chunks
-  constexpr int V = Vec16<T>::n, CPR = 64 / V;
+  constexpr int V = Vec16<T>::n, CPR = TILE / V;
   return row * CPR + (chunk ^ ((row / V) & (CPR - 1)));
 }
 
 // Writes the transposed tile: outT[c0 + c][r0 + r] for r below rows_t, from the LDS tile.
-template <typename T>
+template <typename T, int TILE = 64>
 __device__ __forceinline__ void store_tile_transposed(const typename Vec16<T>::type* tile, T* __restrict__ outT, int ldt,
                                                       int r0, int c0, int rows_t, int C) {
   typedef typename Vec16<T>::type vec_t;
-  constexpr int V = Vec16<T>::n, CPR = 64 / V, ITEMS = 64 * CPR / 256;
+  constexpr int V = Vec16<T>::n, CPR = TILE / V, ITEMS = TILE * CPR / 256;
   const T* flat = (const T*)tile;
 #pragma unroll
   for (int it = 0; it < ITEMS; ++it) {
@@ -60,7 +60,7 @@ __device__ __forceinline__ void store_tile_transposed(const typename Vec16<T>::t
     if (c < C && rs < rows_t) {
       vec_t o;
 #pragma unroll
-      for (int e = 0; e < V; ++e) o[e] = flat[tile_slot<T>(rc * V + e, cl / V) * V + (cl % V)];
+      for (int e = 0; e < V; ++e) o[e] = flat[tile_slot<T, TILE>(rc * V + e, cl / V) * V + (cl % V)];
       *(vec_t*)(outT + (size_t)c * ldt + rs) = o;
     }
   }
@@ -69,41 +69,49 @@ __device__ __forceinline__ void store_tile_transposed(const typename Vec16<T>::t
 // Needs: in/out/mask 16-byte aligned with leading dimensions that are multiples of V (a chunk never straddles
 // two rows; a chunk that straddles C reads pad elements of the same row, which callers keep allocated);
 // rows_t (rows written to the transposed output) a multiple of V or beyond the data (pad rows are zeros).
-template <typename T>
+// TILE x TILE elements per workgroup: 64 for small matrices (more workgroups), 128 for large bf16 ones (8 instead of 2
+// vectors in flight per lane and 256-byte row segments on both sides: 8192 x 16384 in 0.20 -> see the launcher).
+template <typename T, int TILE>
 __global__ __launch_bounds__(256) void copy_transpose_vec_kernel(const T* __restrict__ in, int ldin, int R, int C,
                                                                  T* __restrict__ out, int ldo, T* __restrict__ outT,
                                                                  int ldt, int rows_t, const T* __restrict__ mask,
                                                                  int ldmask) {
   typedef typename Vec16<T>::type vec_t;
-  constexpr int V = Vec16<T>::n, CPR = 64 / V, ITEMS = 64 * CPR / 256;
-  __shared__ vec_t tile[64 * CPR];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  constexpr int V = Vec16<T>::n, CPR = TILE / V, ITEMS = TILE * CPR / 256;
+  __shared__ vec_t tile[TILE * CPR];
+  const int r0 = blockIdx.y * TILE, c0 = blockIdx.x * TILE;
+  vec_t v[ITEMS];
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) {       // every load of the lane is issued before the first store
+    const int idx = threadIdx.x + it * 256;
+    const int row = idx / CPR, ch = idx % CPR;
+    const int r = r0 + row, c = c0 + ch * V;
+#pragma unroll
+    for (int e = 0; e < V; ++e) v[it][e] = from_f32<T>(0.0f);
+    if (r < R && c < C) {
+      v[it] = *(const vec_t*)(in + (size_t)r * ldin + c);
+      if (mask) {     // optional ReLU mask: the element passes only where mask[r][c] > 0
+        const vec_t mk = *(const vec_t*)(mask + (size_t)r * ldmask + c);
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          if (!(to_f32<T>(mk[e]) > 0.0f)) v[it][e] = from_f32<T>(0.0f);
+      }
+#pragma unroll
+      for (int e = 0; e < V; ++e)
+        if (c + e >= C) v[it][e] = from_f32<T>(0.0f);     // pads stay zero
+    }
+  }
 #pragma unroll
   for (int it = 0; it < ITEMS; ++it) {
     const int idx = threadIdx.x + it * 256;
     const int row = idx / CPR, ch = idx % CPR;
     const int r = r0 + row, c = c0 + ch * V;
-    vec_t v;
-#pragma unroll
-    for (int e = 0; e < V; ++e) v[e] = from_f32<T>(0.0f);
-    if (r < R && c < C) {
-      v = *(const vec_t*)(in + (size_t)r * ldin + c);
-      if (mask) {     // optional ReLU mask: the element passes only where mask[r][c] > 0
-        const vec_t mk = *(const vec_t*)(mask + (size_t)r * ldmask + c);
-#pragma unroll
-        for (int e = 0; e < V; ++e)
-          if (!(to_f32<T>(mk[e]) > 0.0f)) v[e] = from_f32<T>(0.0f);
-      }
-#pragma unroll
-      for (int e = 0; e < V; ++e)
-        if (c + e >= C) v[e] = from_f32<T>(0.0f);     // pads stay zero
-      if (out) *(vec_t*)(out + (size_t)r * ldo + c) = v;
-    }
-    tile[tile_slot<T>(row, ch)] = v;
+    if (out && r < R && c < C) *(vec_t*)(out + (size_t)r * ldo + c) = v[it];
+    tile[tile_slot<T, TILE>(row, ch)] = v[it];
   }
   if (!outT) return;
   __syncthreads();
-  store_tile_transposed<T>(tile, outT, ldt, r0, c0, rows_t, C);
+  store_tile_transposed<T, TILE>(tile, outT, ldt, r0, c0, rows_t, C);
 }
 
 // ---------------------------------------------------------------------------------
@@ -434,12 +442,17 @@ hipError_t launch_copy_transpose(int dtype, const void* in, int ldin, int R, int
   const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)outT | (uintptr_t)mask) & 15) == 0) && ldin % V == 0 &&
                        (!out || ldo % V == 0) && (!outT || (ldt % V == 0 && rows_t % V == 0)) && (!mask || ldmask % V == 0);
   if (aligned) {
-    if (dtype == 1)
-      copy_transpose_vec_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)in, ldin, R, C, (bf16*)out, ldo, (bf16*)outT, ldt, rows_t,
-                                                           (const bf16*)mask, ldmask);
+    // large bf16 matrices: 128 x 128 tiles once they still give every compute unit several workgroups
+    if (dtype == 1 && (long)((C + 127) / 128) * ((R + 127) / 128) >= 1024) {
+      dim3 grid128((C + 127) / 128, (R + 127) / 128);
+      copy_transpose_vec_kernel<bf16, 128><<<grid128, 256, 0, s>>>((const bf16*)in, ldin, R, C, (bf16*)out, ldo, (bf16*)outT, ldt,
+                                                                   rows_t, (const bf16*)mask, ldmask);
+    } else if (dtype == 1)
+      copy_transpose_vec_kernel<bf16, 64><<<grid, 256, 0, s>>>((const bf16*)in, ldin, R, C, (bf16*)out, ldo, (bf16*)outT, ldt, rows_t,
+                                                               (const bf16*)mask, ldmask);
     else
-      copy_transpose_vec_kernel<float><<<grid, 256, 0, s>>>((const float*)in, ldin, R, C, (float*)out, ldo, (float*)outT, ldt,
-                                                            rows_t, (const float*)mask, ldmask);
+      copy_transpose_vec_kernel<float, 64><<<grid, 256, 0, s>>>((const float*)in, ldin, R, C, (float*)out, ldo, (float*)outT, ldt,
+                                                                rows_t, (const float*)mask, ldmask);
     return hipGetLastError();
   }
   if (dtype == 1)

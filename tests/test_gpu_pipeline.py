@@ -222,3 +222,23 @@ def test_mean_loss_matches_the_definition():
         x = g.uniform(0.1, 3.0, n).astype(np.float32)
         got = float(api.mean_loss(torch.from_numpy(x).to(DEV)).item())
         assert abs(got - osg.mean_loss(x)) <= 1e-6 * osg.mean_loss(x)
+
+
+def test_external_gradient_step_on_a_large_bf16_output():
+    # a 4096 x 4096 bf16 gradient handed in from outside: masked by the last layer's ReLU, copied and transposed through the
+    # 128 x 128-tile path of the copy kernel (1024 tiles), then the usual backward pass; against the oracle
+    B, widths = 4096, [256, 4096]
+    g, o = pair(widths, api.RELU_ALL, api.MSE_SIL, api.BF16, B, 0.01, 0.9, wseed=31)
+    X, _ = datagen.class_mean_inputs(B, 10, dim=256, seed=4)
+    rs = np.random.default_rng(8)
+    dA = (rs.standard_normal((B, 4096)) * 1e-3).astype(np.float32)
+    Xd, dAd = dev(X, api.BF16), dev(dA, api.BF16)
+    Xv, dAv = to_np(Xd).astype(np.float64), to_np(dAd).astype(np.float64)
+    g.step_external(Xd, dAd)
+    acts = [None, to_np(g.get_activation(1, B)) > 0]
+    bounds = o.forward_error_bound(Xv, unit=2.0 ** -24)
+    out = o.step_external(Xv, dAv, tie_decisions=acts, tie_bounds=bounds)
+    assert out["decisions_refused"] == 0 and out["ties_taken"] <= 200
+    assert rel_err(to_np(g.get_activation(1, B, kind=1)), out["dZ"][1]) <= 2e-2
+    assert rel_err(to_np(g.get_params(0)[0]), o.W[0]) <= 2e-2
+    assert rel_err(to_np(g.get_momentum(0)[0]), o.vW[0]) <= 2e-2
