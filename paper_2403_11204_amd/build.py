@@ -69,6 +69,21 @@ def build(verbose=True):
     return OUT
 
 
+def build_tools(verbose=True):
+    """Development tools beside the library: the stand-alone matrix-product timer (csrc/gemm_bench.hip)."""
+    os.makedirs(BUILD, exist_ok=True)
+    out = os.path.join(BUILD, "gemm_bench")
+    cmd = [hipcc()] + [a for a in COMMON if a != "-fPIC"] + [os.path.join(CSRC, "gemm_bench.hip"), "-o", out]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on gemm_bench.hip:\n%s" % r.stdout)
+    return out
+
+
 if __name__ == "__main__":
     build(verbose="-q" not in sys.argv)
     print("built", OUT)
+    if "--tools" in sys.argv:
+        print("built", build_tools(verbose="-q" not in sys.argv))
