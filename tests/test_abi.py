@@ -113,6 +113,34 @@ def test_free_functions_reject_bad_arguments():
     assert L.slp_probe_mfma_rate(1, 10, dummy, 1 << 22, None, None, None) == -1
 
 
+def test_inference_and_switch_calls_reject_bad_arguments():
+    L = api.lib()
+    dummy = ctypes.c_void_p(0x1000)
+    # accuracy count: null pointers, sizes, dtype, scratch too small or misaligned -- all before any launch
+    assert L.slp_count_correct(None, dummy, 8, 4, 0, dummy, 64, 0, dummy, None) == -1
+    assert L.slp_count_correct(dummy, dummy, 0, 4, 0, dummy, 64, 0, dummy, None) == -1
+    assert L.slp_count_correct(dummy, dummy, 8, 4, 9, dummy, 64, 0, dummy, None) == -1
+    assert L.slp_count_correct(dummy, dummy, 9, 4, 0, dummy, 8, 0, dummy, None) == -3          # 3 partial counts need 12 bytes
+    assert L.slp_count_correct(dummy, dummy, 8, 4, 0, ctypes.c_void_p(0x1002), 64, 0, dummy, None) == -3
+    # the allocation-free variant: same argument checks, and its row limit
+    assert L.slp_count_correct_static(dummy, None, 8, 4, 0, 0, dummy, None) == -1
+    assert L.slp_count_correct_static(dummy, dummy, 8, -1, 0, 0, dummy, None) == -1
+    assert L.slp_count_correct_static(dummy, dummy, 65537, 4, 1, 0, dummy, None) == -2
+    assert b"65536" in L.slp_last_error()
+    assert L.slp_mean_loss(None, 4, dummy, None) == -1
+    assert L.slp_mean_loss(dummy, 0, dummy, None) == -1
+    # switches on a handle
+    assert L.slp_segment_set_fused_update(None, 1) == -1
+    rc, h = _create([8, 4])
+    assert rc == 0
+    assert L.slp_segment_set_fused_update(h, -3) == -1
+    assert L.slp_segment_set_fused_update(h, 2) == 0
+    n = ctypes.c_int64()
+    assert L.slp_segment_target_errors(h, ctypes.byref(n), None) == -5                           # not bound
+    assert L.slp_segment_target_errors(None, ctypes.byref(n), None) == -1
+    L.slp_segment_destroy(h)
+
+
 def test_header_is_plain_c(tmp_path):
     # the boundary is C: the header must compile as C99 on its own, and a C caller must link against the library
     import shutil
