@@ -227,6 +227,53 @@ def measure_segment_peaks(cfg, steps=3):
     return peaks
 
 
+def pipeline_phases(cfg, reps=5):
+    """The other phases of the paper's procedure at the main workload's shape (Sec. 2, Sec. 5), timed with events on
+    the current stream: the forward-only pass that stores the left partition's response, and one recovery step (left
+    forward, input gradient of the frozen right partition, left step from that gradient)."""
+    dt, B, classes = cfg["dtype"], cfg["batch"], cfg["classes"]
+    (wl, al, ll, dist, seed), (wr, ar, lr_, _, _) = cfg["segs"][0], cfg["segs"][-1]
+    left = api.Segment(wl, al, ll, max_batch=B, dtype=dt, lr=cfg["lr"], momentum=cfg["mom"])
+    right = api.Segment(wr, ar, lr_, max_batch=B, dtype=dt, lr=cfg["lr"], momentum=cfg["mom"], input_grad=True)
+    left.init(100)
+    right.init(101)
+    left.set_labels(api.make_synthetic_labels(seed, classes, wl[-1], dist, cfg.get("kappa", 1.0), api.F32))
+    X, y = datagen.class_mean_inputs(B, classes, dim=wl[0], seed=1)
+    tdt = torch.bfloat16 if dt == api.BF16 else torch.float32
+    Xd, yd = torch.from_numpy(X).cuda().to(tdt).contiguous(), torch.from_numpy(y).cuda()
+    resp = torch.empty((B, wl[-1]), dtype=tdt, device="cuda")
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def recovery():
+        left.forward(Xd, out=resp)
+        d_resp, _ = right.input_grad(resp, yd)
+        left.step_external(Xd, d_resp)
+
+    fwd_ms = timed(lambda: left.forward(Xd, out=resp))
+    rec_ms = timed(recovery)
+    P = lambda w: sum(w[i] * w[i + 1] for i in range(len(w) - 1))
+    fwd_fl = 2.0 * P(wl) * B
+    # recovery: left forward twice (response, then inside the step), right forward + every data gradient, left backward
+    rec_fl = (2.0 * P(wl) + 2.0 * P(wl) + 4.0 * P(wr) + (4.0 * P(wl) - 2.0 * wl[0] * wl[1])) * B
+    out = {"store_response": {"segment": wl, "ms_per_batch": fwd_ms, "samples_per_s": B / (fwd_ms * 1e-3),
+                              "tflops": fwd_fl / (fwd_ms * 1e-3) / 1e12},
+           "recovery_step": {"left": wl, "right_frozen": wr, "ms_per_step": rec_ms, "samples_per_s": B / (rec_ms * 1e-3),
+                             "tflops": rec_fl / (rec_ms * 1e-3) / 1e12}}
+    del left, right
+    torch.cuda.empty_cache()
+    return out
+
+
 def quick_config(cid, steps, warmup):
     """ms per step, TFLOP/s and fractions of another configuration, measured the same way as the main workload."""
     cfg = dict(CONFIGS[cid])
@@ -395,6 +442,8 @@ def main():
         ys = None
         torch.cuda.empty_cache()
         out["other_configs"] = [quick_config(2, 200, 20), quick_config(3, 10, 3)]
+        # the forward-only pass and the recovery step of the paper's procedure at this configuration's shape
+        out["pipeline_phases"] = pipeline_phases(cfg)
 
     if not args.no_cpu:
         rows = args.cpu_rows or {0: 64, 1: 256, 2: 256, 3: 256, 4: 256, 5: 1410}[args.config]
