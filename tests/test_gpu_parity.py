@@ -394,12 +394,15 @@ def test_tiny_config_epoch_loss_curve():
 
 
 def test_paper_shaped_config_epoch_loss_curve():
-    # paper-shaped config: 112,800 inputs with 47 balanced classes, batch 256 (441 steps, the last one ragged with
-    # 160 rows), lr 0.01, momentum 0.9, float32, both segments; ONE epoch of the five the configuration names (the
-    # oracle walks it in float64 at ~15 steps a second).  The two sides run free: no state and no ReLU decision
-    # crosses over, so the bar is the single step's 1e-5 widened for a walk of 441 float32 steps with momentum
-    # (rounding differences of one step are carried by the momentum for ~10 steps and add up along the walk).
-    N, B = 112800, 256
+    # paper-shaped config: 112,800 inputs with 47 balanced classes, batch 256 (441 steps per epoch, the last one ragged
+    # with 160 rows), lr 0.01, momentum 0.9, float32, both segments, all FIVE epochs the configuration names (2205 steps;
+    # the oracle walks them in float64 at ~30 steps a second).  The two sides run free: no state and no ReLU decision
+    # crosses over.  What separates them is not rounding as such but the handful of ReLU units per step that the two
+    # sides see on different sides of zero: each sends one sample's gradient into a row of dW on one side only, the
+    # momentum carries it for ~10 steps, and the kicks diffuse along the walk (measured: per-step loss difference 2e-6
+    # after one epoch, 7e-5 / 2e-4 for the two segments after five).  The bars here are therefore wider than the
+    # single step's derived 1e-5 and empirical: 5e-4 on every step's loss, 1e-4 on the epoch means.
+    N, B, EPOCHS = 112800, 256, 5
     X, y = datagen.class_mean_inputs(N, 47, dim=784, seed=1)
     table = orng.make_synthetic_labels(11, 47, 512, api.NORMAL)
     gA, oA = make_pair([784, 1024, 1024, 512], api.RELU_ALL, api.MSE_SIL, api.F32, B, 0.01, 0.9, wseed=3)
@@ -407,33 +410,39 @@ def test_paper_shaped_config_epoch_loss_curve():
     gA.set_labels(torch.from_numpy(table).to(DEV))
     XB = orng.make_segment_inputs(5, table, y, 0, 0.05)
     Xd, XBd, yd = torch.from_numpy(X).to(DEV), torch.from_numpy(XB).to(DEV), torch.from_numpy(y).to(DEV)
-    steps = list(range(0, N, B))
+    steps = [s for _ in range(EPOCHS) for s in range(0, N, B)]
     la = torch.zeros(len(steps), device=DEV)
     lb = torch.zeros(len(steps), device=DEV)
     for i, s in enumerate(steps):
-        la[i] = gA.step(Xd[s:s + B], yd[s:s + B])[0]
-        lb[i] = gB.step(XBd[s:s + B], yd[s:s + B])[0]
-    ra = np.array([oA.step(X[s:s + B].astype(np.float64), y[s:s + B], table)["loss"] for s in steps])
-    rb = np.array([oB.step(XB[s:s + B].astype(np.float64), y[s:s + B])["loss"] for s in steps])
+        gA.step(Xd[s:s + B], yd[s:s + B], loss_out=la[i:i + 1])
+        gB.step(XBd[s:s + B], yd[s:s + B], loss_out=lb[i:i + 1])
+    Xv, XBv = X.astype(np.float64), XB.astype(np.float64)
+    ra = np.array([oA.step(Xv[s:s + B], y[s:s + B], table)["loss"] for s in steps])
+    rb = np.array([oB.step(XBv[s:s + B], y[s:s + B])["loss"] for s in steps])
     ea = float(np.max(np.abs(la.cpu().numpy() - ra) / ra))
     eb = float(np.max(np.abs(lb.cpu().numpy() - rb) / rb))
-    print("loss curves over %d steps: worst relative difference A %.2e, B %.2e; epoch means %.6f / %.6f" %
-          (len(steps), ea, eb, ra.mean(), rb.mean()), flush=True)
-    assert len(steps) == 441 and N - steps[-1] == 160
-    assert ea <= 2e-4 and eb <= 2e-4
-    assert abs(float(la.mean()) - ra.mean()) <= 1e-5 * ra.mean() and abs(float(lb.mean()) - rb.mean()) <= 1e-5 * rb.mean()
-    assert ra[-20:].mean() < ra[:20].mean() and rb[-20:].mean() < rb[:20].mean()      # both segments learn
+    per = len(steps) // EPOCHS
+    means_g = [(float(la[e * per:(e + 1) * per].mean()), float(lb[e * per:(e + 1) * per].mean())) for e in range(EPOCHS)]
+    means_o = [(ra[e * per:(e + 1) * per].mean(), rb[e * per:(e + 1) * per].mean()) for e in range(EPOCHS)]
+    print("loss curves over %d steps: worst relative difference A %.2e, B %.2e; epoch means %s" %
+          (len(steps), ea, eb, ["%.5f / %.5f" % m for m in means_o]), flush=True)
+    assert per == 441 and N - steps[per - 1] == 160
+    assert ea <= 5e-4 and eb <= 5e-4
+    for (ga, gb), (oa, ob) in zip(means_g, means_o):
+        assert abs(ga - oa) <= 1e-4 * oa and abs(gb - ob) <= 1e-4 * ob
+    assert all(means_o[e + 1][0] < means_o[e][0] and means_o[e + 1][1] < means_o[e][1] for e in range(EPOCHS - 1))   # both learn
     # Weights at the end of the walk.  With nothing crossing over, a ReLU unit whose pre-activation the two sides see
     # on different sides of zero (a handful per step) sends one sample's gradient into a row of dW on one side only;
     # those kicks diffuse along the walk, so single elements drift far more than rounding alone would move them while
-    # the loss curves stay together.  Compared in the Frobenius sense, with a loose bar on the worst element.
+    # the loss curves stay together (measured after five epochs: 2e-4 to 6e-4 in the Frobenius sense, up to 6e-3 on the
+    # worst element).  Compared in the Frobenius sense, with a loose bar on the worst element.
     for g_, o_ in ((gA, oA), (gB, oB)):
         for l in range(3):
             got = to_np(g_.get_params(l)[0]).astype(np.float64)
             fro = float(np.linalg.norm(got - o_.W[l]) / np.linalg.norm(o_.W[l]))
-            print("layer %d: weights after the epoch, relative Frobenius difference %.2e, worst element %.2e" %
+            print("layer %d: weights after the walk, relative Frobenius difference %.2e, worst element %.2e" %
                   (l, fro, rel_err(got, o_.W[l])), flush=True)
-            assert fro <= 2e-4 and rel_err(got, o_.W[l]) <= 5e-3
+            assert fro <= 2e-3 and rel_err(got, o_.W[l]) <= 2e-2
 
 
 @pytest.mark.parametrize("dtype", [api.F32, api.BF16])
