@@ -320,6 +320,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=None)
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run one plain 1 GiB -> 1 GiB elementwise copy kernel (scale reference for HBM byte counters)")
+    ap.add_argument("--graph", action="store_true", help="replay captured steps on a configuration that launches eagerly by default")
     ap.add_argument("--eager", action="store_true", help="configs 0-2: launch every kernel of a step instead of replaying graphs")
     ap.add_argument("--fused", type=int, nargs="?", const=1, default=0, help="apply the update in the epilogue of the weight-gradient products")
     ap.add_argument("--unfused", action="store_true", help="configs 0-2 and 5: separate update launches instead of the fused update")
@@ -337,6 +338,8 @@ def main():
     cfg = dict(CONFIGS[args.config])
     if cfg.get("graph"):         # small and mid-size layers: the update inside the weight-gradient products (rule 2)
         cfg["fused"] = 2
+    if args.graph:
+        cfg["graph"] = True
     if args.fused:
         cfg["fused"] = args.fused
     if args.unfused:
@@ -366,7 +369,7 @@ def main():
         # graphs cannot be captured on the null stream; the matrix products are timed in a second, eager pass
         # (launch-by-launch events and replayed graphs exclude each other)
         with torch.cuda.stream(torch.cuda.Stream()):
-            wall_ms, ev_ms, _ = time_workload(segs, inputs, ys, False, steps, warmup, profile=False)
+            wall_ms, ev_ms, _ = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup, profile=False)
             prof_steps = max(steps // 4, 10)
             _, _, prof = time_workload(segs, inputs, ys, False, prof_steps, 2)
     elif args.events_apart:
