@@ -303,6 +303,14 @@ def quick_config(cid, steps, warmup):
            # update (24 B with momentum in bf16 mode: g, v, w read; v, w, bf16 copy, transposed copy written)
            "param_bytes_per_step_algorithmic": 24 * n_params if cfg["dtype"] == api.BF16 else 28 * n_params,
            "hbm_floor_ms": (24 if cfg["dtype"] == api.BF16 else 28) * n_params / HBM_BYTES_PER_S * 1e3}
+    if cfg["streams"]:
+        # the same segments one after another on one stream, update tails overlapped (what `--config N --serial` times)
+        for seg in segs:
+            seg.set_overlap(True)
+        w2, e2, _ = time_workload(segs, inputs, ys, False, steps, warmup, profile=False)
+        ms2 = max(w2, e2)
+        out["one_stream"] = {"ms_per_step": ms2, "samples_per_s": B / (ms2 * 1e-3), "step_tflops": flops_step / (ms2 * 1e-3) / 1e12,
+                             "step_frac_of_mfma_peak": flops_step / (ms2 * 1e-3) / 1e12 / peak}
     del segs, inputs, ys
     torch.cuda.empty_cache()
     return out
