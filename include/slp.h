@@ -235,7 +235,10 @@ int slp_segment_set_fused_update(slp_segment* seg, int on);
  * through this interface see the same values as without overlap (bit for bit).  A caller that reads or frees the
  * parameter or workspace buffers directly must call slp_segment_join first (slp_segment_destroy and slp_segment_bind
  * wait on the host).  No effect on steps that are captured into a graph; a stream that is being captured cannot wait
- * for updates left pending outside the capture: such a call fails with SLP_ERR_STATE.  Turning overlap off waits on
+ * for updates left pending outside the capture: such a call fails with SLP_ERR_STATE.  With overlap on, the weight updates of
+ * large layers are also paced (each of their workgroups pauses between tiles, by an amount that grows with the batch), which
+ * roughly doubles their duration and keeps their memory traffic from stalling the matrix products beside them; the caller is
+ * expected to keep the device busy behind the step, as a loop over segments does.  Turning overlap off waits on
  * the host for pending updates, after which the handle is back to plain stream order.  Off by default.
  * slp_segment_join: makes `stream` wait for updates a previous step left running; a no-op when none are pending. */
 int slp_segment_set_overlap(slp_segment* seg, int on);
