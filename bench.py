@@ -46,10 +46,10 @@ CONFIGS = {
     0: dict(name="tiny 784-128-64 | 64-64-47 fp32", dtype=api.F32, batch=64, classes=47, lr=0.01, mom=0.0, streams=False, graph=True,
             segs=[([784, 128, 64], ALL, MSE, api.UNIFORM_PM1, 7), ([64, 64, 47], LAST, CE, None, None)]),
     1: dict(name="paper-shaped 784-1024-1024-512 | 512-1024-1024-47 fp32", dtype=api.F32, batch=256, classes=47, lr=0.01,
-            mom=0.9, streams=False, graph=True,
+            mom=0.9, streams=True, graph=True,
             segs=[([784, 1024, 1024, 512], ALL, MSE, api.NORMAL, 11), ([512, 1024, 1024, 47], LAST, CE, None, None)]),
     2: dict(name="wide 784-4096-4096-2048 | 2048-4096-4096-47 bf16", dtype=api.BF16, batch=1024, classes=47, lr=0.01,
-            mom=0.9, streams=False, graph=True,
+            mom=0.9, streams=True, graph=True,
             segs=[([784, 4096, 4096, 2048], ALL, MSE, api.BINARY_PM1, 13), ([2048, 4096, 4096, 47], LAST, CE, None, None)]),
     3: dict(name="deep 12x8192 in 4 segments on 4 streams bf16", dtype=api.BF16, batch=4096, classes=100, lr=0.01, mom=0.9,
             streams=True,
@@ -61,7 +61,7 @@ CONFIGS = {
                   ([16384, 16384, 16384, 1000], LAST, CE, None, None)]),
     # the network of the paper's own experiment (Sec. 3): 784-80-60 | 60-60-60-47, batch 1410, labels 10 * U(0,1)
     5: dict(name="paper Sec. 3 network 784-80-60 | 60-60-60-47 fp32", dtype=api.F32, batch=1410, classes=47, lr=0.01, mom=0.9,
-            streams=False, graph=True, kappa=10.0,
+            streams=True, graph=True, kappa=10.0,
             segs=[([784, 80, 60], ALL, MSE, api.UNIFORM01, 3), ([60, 60, 60, 47], LAST, CE, None, None)]),
 }
 E2E_WIDTHS = [784, 16384, 16384, 16384, 16384, 16384, 1000]
@@ -284,7 +284,7 @@ def quick_config(cid, steps, warmup):
     torch.cuda.synchronize()
     if cfg.get("graph"):
         with torch.cuda.stream(torch.cuda.Stream()):
-            wall_ms, ev_ms, _ = time_workload(segs, inputs, ys, False, steps, warmup, profile=False)
+            wall_ms, ev_ms, _ = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup, profile=False)
             _, _, prof = time_workload(segs, inputs, ys, False, max(steps // 4, 10), 2)
     else:
         wall_ms, ev_ms, prof = time_workload(segs, inputs, ys, cfg["streams"], steps, warmup)
@@ -296,7 +296,7 @@ def quick_config(cid, steps, warmup):
     out = {"workload": cfg["name"], "global_batch": B, "steps": steps, "ms_per_step": ms, "samples_per_s": B / (ms * 1e-3),
            "step_tflops": flops_step / (ms * 1e-3) / 1e12, "step_frac_of_mfma_peak": flops_step / (ms * 1e-3) / 1e12 / peak,
            # launch-by-launch events overlap when the segments run concurrently: no per-kernel rate then
-           "gemm_tflops": gemm_fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 and not cfg["streams"] else None,
+           "gemm_tflops": gemm_fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 and (cfg.get("graph") or not cfg["streams"]) else None,
            "launch": "hip graph replay" if cfg.get("graph") else "eager", "fused_update": cfg.get("fused", 0),
            "concurrent_streams": len(segs) if cfg["streams"] else 1,
            # the other roof: every parameter streams through the step once per product that reads it and through the
@@ -305,8 +305,9 @@ def quick_config(cid, steps, warmup):
            "hbm_floor_ms": (24 if cfg["dtype"] == api.BF16 else 28) * n_params / HBM_BYTES_PER_S * 1e3}
     if cfg["streams"]:
         # the same segments one after another on one stream, update tails overlapped (what `--config N --serial` times)
-        for seg in segs:
-            seg.set_overlap(True)
+        if not cfg.get("graph"):
+            for seg in segs:
+                seg.set_overlap(True)
         w2, e2, _ = time_workload(segs, inputs, ys, False, steps, warmup, profile=False)
         ms2 = max(w2, e2)
         out["one_stream"] = {"ms_per_step": ms2, "samples_per_s": B / (ms2 * 1e-3), "step_tflops": flops_step / (ms2 * 1e-3) / 1e12,
@@ -334,10 +335,10 @@ def main():
     ap.add_argument("--unfused", action="store_true", help="configs 0-2 and 5: separate update launches instead of the fused update")
     ap.add_argument("--events-apart", action="store_true",
                     help="time the steps without per-launch events and the matrix products in a second pass (as the graph configs do)")
-    ap.add_argument("--serial", action="store_true", help="config 3: run the four segments one after another on one stream")
+    ap.add_argument("--serial", action="store_true", help="run the segments one after another on one stream (configs 1, 2, 3, 5 default to a stream each)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="end every step by waiting for its parameter updates (slp_segment_set_overlap off)")
-    ap.add_argument("--concurrent", action="store_true", help="run the segments at the same time on a stream each (the default of config 3)")
+    ap.add_argument("--concurrent", action="store_true", help="run the segments at the same time on a stream each (the default of configs 1, 2, 3, 5)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (segments are independent jobs; no collectives exist): use --gpus 1")
