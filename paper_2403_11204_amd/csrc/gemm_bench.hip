@@ -1,5 +1,5 @@
 // Stand-alone timing of one matrix product of the segment step (the three products of paper Sec. 2-3 all run through
-// launch_gemm): random bf16 operands, `iters` launches after two warm-up launches, 64 sampled outputs checked against
+// launch_gemm): random bf16 operands, `iters` launches after 0.3 s of warm-up launches, 64 sampled outputs checked against
 // float64 dot products on the host, and -- with both output layouts -- the transposed output checked against the
 // row-major one element by element.  A development tool: nothing in the library or the tests uses it.
 //
@@ -11,6 +11,7 @@
 //     data    : 0 uniform(-1,1), 1 zeros, 2 half zeros (ReLU-like), 3 quarter steps
 //     outputs : 0 row-major and transposed, 1 row-major only, 2 transposed only (epilogues 0 and 1)
 #include "gemm.hip"
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <vector>
@@ -41,8 +42,17 @@ int main(int argc, char** argv) {
   g.C = dC; g.CT = dCT; g.ldc = ldc; g.ldct = ldct; g.bias = dBias; g.relu = 0; g.maskT = dMask; g.ldmask = ldct; g.Cf = dCf;
   if (outs == 1) g.CT = nullptr; if (outs == 2) g.C = nullptr;
   hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
-  for (int i = 0; i < 2; i++) CK(slp::launch_gemm(1, epi, g, 0));
-  CK(hipDeviceSynchronize());
+  // warm-up: at least two launches and at least 0.3 s of them -- the chip's clock settles over the first ~0.1 s of a
+  // burst of work, and a short product timed before that reads 10-25 % low
+  {
+    const auto t0 = std::chrono::steady_clock::now();
+    int n = 0;
+    do {
+      for (int i = 0; i < 2; i++) CK(slp::launch_gemm(1, epi, g, 0));
+      CK(hipDeviceSynchronize());
+      n += 2;
+    } while (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() < 0.3 && n < 100000);
+  }
   CK(hipEventRecord(e0, 0));
   for (int i = 0; i < iters; i++) CK(slp::launch_gemm(1, epi, g, 0));
   CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1));
