@@ -72,8 +72,10 @@ struct slp_segment {
   std::vector<Layer> layers;
   size_t param_bytes, work_bytes;
   // workspace offsets / pointers, index = layer 0..L
-  std::vector<size_t> oA, oAT, odZ, odZT;
+  std::vector<size_t> oA, oAT, odZ, odZT, oBits;
   std::vector<void*> A, AT, dZ, dZT;
+  std::vector<uint32_t*> bits;   // bf16 mode: [A_l > 0] of the hidden activations, one bit per element (GemmArgs::bits)
+  int ldbits;
   size_t oPartials, oLoss, oBadIds;
   int n_partials;
   float *partials, *loss_dev;
@@ -176,6 +178,7 @@ int forward_layers(slp_segment* s, int batch, bool training, hipStream_t st, con
     g.C = s->A[l]; g.ldc = s->ldw[l];
     if (l == s->L && out_direct) { g.C = out_direct; g.ldc = s->widths[l]; }
     g.CT = (training && l < s->L) ? s->AT[l] : nullptr; g.ldct = s->ldb;
+    g.bits_out = (training && l < s->L) ? s->bits[l] : nullptr; g.ldbits = s->ldbits;
     g.bias = ly.b; g.relu = relu_on(s, l) ? 1 : 0;
     int rc = run_gemm(s, EPI_FWD, g, st);
     if (rc) return rc;
@@ -210,6 +213,7 @@ int data_gradient(slp_segment* seg, int l, int batch, hipStream_t st) {
   g.C = seg->dZ[l - 1]; g.ldc = seg->ldw[l - 1];
   g.CT = l > 1 ? seg->dZT[l - 1] : nullptr; g.ldct = seg->ldb;
   g.maskT = l > 1 ? seg->AT[l - 1] : nullptr; g.ldmask = seg->ldb;
+  g.bits = l > 1 ? seg->bits[l - 1] : nullptr; g.ldbits = seg->ldbits;
   return run_gemm(seg, EPI_DGRAD, g, st);
 }
 
@@ -427,10 +431,12 @@ int slp_segment_create(const int* widths, int n_widths, int act, int loss, const
   s->param_bytes = off;
 
   off = 0;
-  s->oA.assign(s->L + 1, (size_t)-1); s->oAT = s->oA; s->odZ = s->oA; s->odZT = s->oA;
+  s->oA.assign(s->L + 1, (size_t)-1); s->oAT = s->oA; s->odZ = s->oA; s->odZT = s->oA; s->oBits = s->oA;
+  s->ldbits = (s->max_batch + 127) / 128 * 4;
   for (int l = 0; l <= s->L; ++l) {
     s->oA[l] = take((size_t)s->max_batch * s->ldw[l] * es);
     if (l < s->L) s->oAT[l] = take((size_t)s->widths[l] * s->ldb * es);
+    if (l >= 1 && l < s->L && s->dtype == SLP_BF16) s->oBits[l] = take((size_t)s->widths[l] * s->ldbits * 4);
     if (l == 0 && s->input_grad) s->odZ[0] = take((size_t)s->max_batch * s->ldw[0] * es);
     if (l >= 1) {
       // row-major dZ_l is the A operand of layer l's data gradient: needed for l >= 2, for the loss
@@ -498,10 +504,11 @@ int slp_segment_bind(slp_segment* seg, void* params, size_t params_bytes, void* 
   }
   char* w = (char*)workspace;
   auto at = [&](size_t o) -> void* { return o == (size_t)-1 ? nullptr : (void*)(w + o); };
-  seg->A.clear(); seg->AT.clear(); seg->dZ.clear(); seg->dZT.clear();
+  seg->A.clear(); seg->AT.clear(); seg->dZ.clear(); seg->dZT.clear(); seg->bits.clear();
   for (int l = 0; l <= seg->L; ++l) {
     seg->A.push_back(at(seg->oA[l])); seg->AT.push_back(at(seg->oAT[l]));
     seg->dZ.push_back(at(seg->odZ[l])); seg->dZT.push_back(at(seg->odZT[l]));
+    seg->bits.push_back((uint32_t*)at(seg->oBits[l]));
   }
   seg->partials = (float*)at(seg->oPartials);
   seg->loss_dev = (float*)at(seg->oLoss);

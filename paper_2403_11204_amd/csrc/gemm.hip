@@ -597,9 +597,18 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
     // 8192 x 16384 products -4 % at K = 1024, -0.5 % at K = 16384.
     static_assert(NW == 8, "the staged epilogue is laid out for 8 wavefronts of 128 x 64");
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+    const int rowW = m0 + wm * 128, colW = n0 + wn * WTN;     // origin of this wavefront's sub-tile
+    // data gradient with the mask as bits: the 32 bits a lane needs per accumulator column are one dword
+    uint32_t mbits[NB];
+    if (EPI == EPI_DGRAD && g.bits) {
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int n = colW + j * 16 + lrow;
+        mbits[j] = (n < g.N && rowW < g.M) ? g.bits[(size_t)n * g.ldbits + (rowW >> 5) + lgrp] : 0u;   // rowW >= M: no such block in the row
+      }
+    }
     __syncthreads();   // every wavefront's (zero-fill) loads have landed and its fragment reads are over
     unsigned char* reg = smem + w * 16384;
-    const int rowW = m0 + wm * 128, colW = n0 + wn * WTN;     // origin of this wavefront's sub-tile
     const int Mr = (g.M + 7) & ~7;
     // finish the values in place: bias + ReLU, zeros outside the matrix
 #pragma unroll
@@ -608,6 +617,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
       const bool col_ok = n < g.N;
       float bias = 0.0f;
       if (EPI == EPI_FWD && col_ok) bias = g.bias[n];
+      uint32_t word = 0;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int mb = rowW + i * 16 + 4 * lgrp;
@@ -617,6 +627,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
             acc[i][j][e] += bias;
             if (g.relu) acc[i][j][e] = fmaxf(acc[i][j][e], 0.0f);
           }
+        } else if (g.bits) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (!((mbits[j] >> (4 * i + e)) & 1u)) acc[i][j][e] = 0.0f;
         } else if (g.maskT && col_ok && mb < Mr) {
           const bf16x4 mk = *(const bf16x4*)((const bf16*)g.maskT + (size_t)n * g.ldmask + mb);
 #pragma unroll
@@ -626,7 +640,15 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           if (mb + e >= g.M || !col_ok) acc[i][j][e] = 0.0f;
+        if (EPI == EPI_FWD) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) word |= (uint32_t)((float)(bf16)acc[i][j][e] > 0.0f) << (4 * i + e);
+          __builtin_amdgcn_sched_barrier(0);     // one block's conversions at a time: hoisted together they cost registers
+        }
       }
+      // the mask the data gradient of the layer above will need: one bit per stored (bf16-rounded) output > 0
+      if (EPI == EPI_FWD && g.bits_out && col_ok && rowW < g.M) g.bits_out[(size_t)n * g.ldbits + (rowW >> 5) + lgrp] = word;
+      __builtin_amdgcn_sched_barrier(0);
     }
     auto pack4 = [](float a, float b, float c, float d) {
       const bf16x4 o = {(bf16)a, (bf16)b, (bf16)c, (bf16)d};

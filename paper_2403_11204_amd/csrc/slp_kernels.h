@@ -46,6 +46,14 @@ struct GemmArgs {
   int relu;
   const void* maskT;  // [N][ldmask], element type T
   int ldmask;
+  // The same mask as one bit per element, for products that run on the 256x256 bf16 tile (every other tile configuration
+  // ignores both pointers): EPI_FWD writes bits_out, EPI_DGRAD reads bits instead of maskT when it is not null.
+  // Row n holds ldbits dwords; dword 4 * (m / 128) + g carries, at bit 4 i + e, the element m = 128 (m / 128) + 16 i + 4 g + e
+  // (g = 0..3, i = 0..7, e = 0..3: the elements one lane of the tile's accumulator layout holds), set where the stored
+  // output is > 0.  ldbits >= 4 * ceil(M / 128); both products must have the same M and N.
+  uint32_t* bits_out;
+  const uint32_t* bits;
+  int ldbits;
   float* Cf;       // [M][ldc] float32
   // EPI_WGRAD_UPDATE: the gradient never goes to memory; the epilogue applies the optimiser step to the tile it holds
   // (paper Sec. 3: SGD with momentum), v = mu v + acc; w -= lr v, on the float32 master weights uW and momentum uV
