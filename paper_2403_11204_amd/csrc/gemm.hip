@@ -591,10 +591,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
     // workgroup barrier after the first one (LDS operations of one wavefront execute in order).  16-byte chunk c of
     // a staged row r sits at chunk c ^ (r & 15) (transposed) / c ^ ((r >> 1) & 7) (row-major), which keeps the
     // 8-byte writes and the 16-byte reads of a wavefront free of bank conflicts.
-    // (The data gradient's ReLU mask is gathered before the staging, 8 bytes per accumulator block; applying it on the
-    // way out instead, from coalesced 16-byte loads of both layouts of the activation, measured 2-3 % slower on short
-    // contractions.)  Against one shared 256 x 512-byte staging area with a workgroup barrier around each pass:
-    // 8192 x 16384 products -4 % at K = 1024, -0.5 % at K = 16384.
+    // The data gradient's ReLU mask comes as bits when the forward product of the layer below ran on this tile too
+    // (GemmArgs::bits: one dword per lane and 16-column block, 4 loads instead of 32 gathered 8-byte pieces of the
+    // transposed activation; the gather was 10 of the epilogue's 17 us per tile), else it is gathered from maskT
+    // before the staging.  (Applying the bf16 mask on the way out instead, from coalesced 16-byte loads of both layouts
+    // of the activation, measured 2-3 % slower on short contractions.)  Against one shared 256 x 512-byte staging area
+    // with a workgroup barrier around each pass: 8192 x 16384 products -4 % at K = 1024, -0.5 % at K = 16384.
     static_assert(NW == 8, "the staged epilogue is laid out for 8 wavefronts of 128 x 64");
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
     const int rowW = m0 + wm * 128, colW = n0 + wn * WTN;     // origin of this wavefront's sub-tile
