@@ -559,13 +559,17 @@ def test_seeded_random_shapes(seed):
     check_step(g, o, X, y, table, dtype, steps=2)
 
 
-@pytest.mark.parametrize("widths,B", [([4000, 4090, 3999], 3900), ([4000, 4400, 4100], 3900)], ids=["regions", "groups"])
-def test_bf16_products_on_the_big_tile_with_ragged_edges(widths, B):
+@pytest.mark.parametrize("widths,B,max_batch", [([4000, 4090, 3999], 3900, 3900), ([4000, 4400, 4100], 3900, 3900),
+                                                ([4000, 4090, 3999], 3850, 4000)], ids=["regions", "groups", "regions-batch-below-max"])
+def test_bf16_products_on_the_big_tile_with_ragged_edges(widths, B, max_batch):
     # every product of these steps has 224 or more 256x256 tiles, so all run through the big bf16 kernel, with ragged
     # last tiles in rows, columns and contraction: 16 x 16 tile grids (walked by regions) in the first case, 16 x 18
-    # and 18 x 17 grids (walked by groups of tile rows) in the second
+    # and 18 x 17 grids (walked by groups of tile rows) in the second.  The hidden layer's ReLU mask travels from the
+    # forward product to the data gradient as bits, 128 batch rows per group of 4 dwords: the last wavefront row of the
+    # tile grid lies wholly beyond the batch in all three cases, and in the third the buffers are laid out for a larger
+    # batch than the step uses.
     X, y, table = case_data(widths, api.MSE_SIL, B, api.NORMAL, 29, seed=12)
-    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, api.BF16, max_batch=B, lr=0.05, mom=0.9, wseed=13)
+    g, o = make_pair(widths, api.RELU_ALL, api.MSE_SIL, api.BF16, max_batch=max_batch, lr=0.05, mom=0.9, wseed=13)
     check_step(g, o, X, y, table, api.BF16)
 
 
