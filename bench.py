@@ -37,7 +37,7 @@ HBM_BYTES_PER_S = 8.0e12                             # published HBM3E rate of M
 # one step of the default workload: rocprofv3 FETCH_SIZE / WRITE_SIZE passes scaled by a 1 GiB copy kernel in
 # the same process (profiles/comparison_config_gemm_hbm_traffic.md).  Valid for the kernel those passes ran;
 # set to None whenever csrc/gemm.hip changes until the passes are repeated.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {4: 5.18e9}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {4: 5.19e9}
 MSE, CE = api.MSE_SIL, api.SOFTMAX_XENT
 ALL, LAST = api.RELU_ALL, api.RELU_HIDDEN_IDENTITY_LAST
 

@@ -502,9 +502,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_nt_big_kernel(const GemmArgs g) 
   auto read_b = [&](int stage, int kk, int c) {
     bfr[kk][c] = *(const u32x4*)(smem + stage * STAGE + fragB + c * 16 * 128 + xo[kk]);
   };
-  auto mma = [&](int h, int kk, int buf, int m) {   // m = 0..4 NB - 1: A fragment m / NB against B fragment m % NB
-    acc[h * 4 + m / NB][m % NB] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-        __builtin_bit_cast(bf16x8, af[buf][m / NB]), __builtin_bit_cast(bf16x8, bfr[kk][m % NB]), acc[h * 4 + m / NB][m % NB], 0, 0, 0);
+  // m = 0..4 NB - 1: A fragment ia = m / NB against the B fragments in turn, forwards for even ia and backwards for
+  // odd ia, so that from one MFMA to the next only one of the two operands changes.  The chip is power-limited under
+  // this load and operand lines that do not toggle cost less: measured +0.8 % on 8192x16384x16384 and 16384x16384x8192
+  // against walking the B fragments forwards every time (three alternating runs each, spread 0.1 %).
+  auto mma = [&](int h, int kk, int buf, int m) {
+    const int ia = m / NB, ib = (ia & 1) ? NB - 1 - m % NB : m % NB;
+    acc[h * 4 + ia][ib] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+        __builtin_bit_cast(bf16x8, af[buf][ia]), __builtin_bit_cast(bf16x8, bfr[kk][ib]), acc[h * 4 + ia][ib], 0, 0, 0);
   };
 #define VMCNT(n) ((((n) & 15) | 0x0F70 | (((n) >> 4) << 14)))
 #define SLP_FENCE() __builtin_amdgcn_sched_barrier(0)
