@@ -325,7 +325,7 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=sorted(CONFIGS))
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-e2e", action="store_true", help="skip the end-to-end backprop comparison (config 4)")
-    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the wide and deep configurations (config 4)")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations (config 4)")
     ap.add_argument("--cpu-rows", type=int, default=None)
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run one plain 1 GiB -> 1 GiB elementwise copy kernel (scale reference for HBM byte counters)")
@@ -450,10 +450,10 @@ def main():
         out["end_to_end_baseline"]["both_segments_resident_peak_bytes"] = out["peak_hbm_bytes_torch"]
 
     if args.config == 4 and not args.no_others:
-        # the other large-width configurations, short runs (their own lines: --config 2 / --config 3)
+        # the other configurations, short runs (their own lines: --config N): wide, deep, paper-shaped, the paper's own network
         ys = None
         torch.cuda.empty_cache()
-        out["other_configs"] = [quick_config(2, 200, 20), quick_config(3, 10, 3)]
+        out["other_configs"] = [quick_config(2, 200, 20), quick_config(3, 10, 3), quick_config(1, 500, 50), quick_config(5, 500, 50)]
         # the forward-only pass and the recovery step of the paper's procedure at this configuration's shape
         out["pipeline_phases"] = pipeline_phases(cfg)
 
