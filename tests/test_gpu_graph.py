@@ -133,3 +133,41 @@ def test_staged_epochs_replay_one_graph_and_match_eager_epochs():
         assert le == lg
         assert same_state(eager, graph)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", [api.F32, api.BF16])
+def test_two_replayed_segments_on_a_stream_each_equal_serial_eager_steps(dtype):
+    # what `bench.py` does for the graph-replayed configurations: the two partitions are independent (paper Sec. 2), so
+    # each replays its own captured step on its own stream, both in flight at once; every step of both must leave the
+    # same bits as eager steps taken one after the other on one stream
+    B, classes, dim = 200, 12, 96
+    wa, wb = [dim, 160, 64], [64, 96, classes]
+    ea, ga = twin(wa, api.RELU_ALL, api.MSE_SIL, dtype, B, wseed=21)
+    eb, gb = twin(wb, api.RELU_HIDDEN_IDENTITY_LAST, api.SOFTMAX_XENT, dtype, B, wseed=22)
+    table = api.make_synthetic_labels(5, classes, wa[-1], api.NORMAL, 1.0)
+    ea.set_labels(table)
+    ga.set_labels(table)
+    ga.set_graph(True)
+    gb.set_graph(True)
+    tdt = torch.bfloat16 if dtype == api.BF16 else torch.float32
+    batches = []
+    for i in range(3):
+        X, y = datagen.class_mean_inputs(B, classes, dim=dim, seed=31, first=i * B)
+        yd = torch.from_numpy(y).to(DEV)
+        Xa = torch.from_numpy(X).to(DEV).to(tdt).contiguous()
+        Xb = (table.to(torch.float32)[yd.long()] + 0.05 * torch.randn(B, wa[-1], device=DEV)).to(tdt).contiguous()
+        batches.append((Xa, Xb, yd))
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for st in (sa, sb):
+        st.wait_stream(torch.cuda.current_stream())
+    for it in range(9):                                   # every batch is captured once, then replayed twice
+        Xa, Xb, yd = batches[it % 3]
+        la_e = ea.step(Xa, yd).clone()
+        lb_e = eb.step(Xb, yd).clone()
+        with torch.cuda.stream(sa):
+            la_g = ga.step(Xa, yd).clone()
+        with torch.cuda.stream(sb):
+            lb_g = gb.step(Xb, yd).clone()
+        torch.cuda.synchronize()
+        assert torch.equal(la_e, la_g) and torch.equal(lb_e, lb_g), it
+        assert same_state(ea, ga) and same_state(eb, gb), it
