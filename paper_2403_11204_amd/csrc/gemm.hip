@@ -12,8 +12,8 @@
 // no transposition on the operand path.
 //
 // gfx950 mapping
-//   * bf16: v_mfma_f32_16x16x32_bf16 (16x16 blocks; a register-only loop of it sustains 2110 TFLOP/s under the
-//     chip's power limit, the 32x32x16 form 1850); float32: v_mfma_f32_32x32x2_f32, four per 16-byte chunk pair.
+//   * bf16: v_mfma_f32_16x16x32_bf16 (16x16 blocks; a register-only loop of it sustains 2000-2100 TFLOP/s under the
+//     chip's power limit, the 32x32x16 form 1800-1850); float32: v_mfma_f32_32x32x2_f32, four per 16-byte chunk pair.
 //     A k-tile is 128 bytes per row for both types (64 bf16 / 32 float), so loads, LDS layout and addressing
 //     are byte-identical for the two types.
 //   * global -> LDS directly (buffer_load_dwordx4 ... lds): no staging registers and no ds_write instructions.
@@ -37,7 +37,8 @@
 //     is one vector store into the transposed output; for the row-major output the quad of lanes holding
 //     4 adjacent columns transposes its 4x4 block with DPP moves, after which a lane holds 4 consecutive
 //     columns of one row: one vector store as well (2 stores per quad instead of 5).
-//     The big kernel's bf16 outputs go through LDS instead and leave as whole 512-byte rows (see its epilogue).
+//     The big kernel's bf16 outputs go through LDS instead and leave as whole 128- and 256-byte row segments
+//     (see its epilogue).
 //   * workgroup -> tile: consecutive workgroup ids go round-robin over the 8 XCDs, so
 //     ids are first regrouped per XCD (each XCD gets a contiguous range of tiles and
 //     its own 4 MB L2 sees a compact set of operand rows), then walked in column-major groups of 8 tile-rows.
